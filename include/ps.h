@@ -1,0 +1,237 @@
+/*
+ * ps.h -- C ABI of a GPU-resident parameter service for gfx950 (MI355X).
+ *
+ * The service does what the paper's aggregation servers do (Section 2,
+ * "Background and Motivation"; Section 3.1, "System Overview"): it hosts the
+ * master copy of every registered job's parameters, collects the gradient
+ * pushes of the job's W workers, aggregates them, updates the master copy with
+ * the aggregated result, and answers pulls.  Aggregations are tensor-scale and
+ * independent of each other (Section 2.3), so they are not grouped by job: one
+ * call aggregates a list of blocks that may belong to many jobs, the way the
+ * paper packs several jobs' aggregations onto one server (Section 3.1).  The
+ * key of a piece of state is (job id, block id), as in Appendix A where the
+ * agent rewrites a tensor's key to (job ID, tensor ID).
+ *
+ * A BLOCK is a contiguous slice of one layer (tensor) of at most
+ * max_block_bytes/4 binary32 values: as many full blocks as fit, then one
+ * remainder block.  Blocks are numbered per job in registration order.
+ *
+ * Arithmetic of one aggregation of a block (binary32, every operation rounded
+ * separately, no fused multiply-add unless PS_FLAG_FP_CONTRACT is set):
+ *     S  = ((g_0 + g_1) + g_2) + ... + g_{W-1}          fixed worker order
+ *     d  = S + wd * p ;   v' = mu * v + d ;   p' = p - lr * v'
+ * and the block's telemetry value sum_i S_i^2 accumulated in binary64.
+ *
+ * Conventions
+ *   - Every function returns a status (PS_OK = 0, errors negative) unless
+ *     stated otherwise.  Nothing throws across this boundary.
+ *   - "device" pointers address GPU memory of the current HIP device; "host"
+ *     pointers address ordinary memory.  The library never takes ownership of a
+ *     pointer passed in.
+ *   - stream arguments are hipStream_t values passed as void* (NULL = the
+ *     default stream).  Device work is enqueued on that stream and not waited
+ *     for; the caller synchronises.
+ *   - One context is guarded by one mutex: calls on the same context may come
+ *     from several threads.  Aggregation, pull and telemetry of a block are
+ *     ordered by the streams the caller uses.
+ */
+#ifndef PS_H_
+#define PS_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_MAX_W 32                 /* most workers per job (push mask is 32 bits) */
+#define PS_DEFAULT_BLOCK_BYTES (4u << 20)
+#define PS_DEFAULT_SMALL_ELEMS 4096u
+#define PS_ALIGN_BYTES 256u          /* alignment of every block inside the arena */
+#define PS_GRAD_ALIGN_BYTES 16u      /* alignment required of pushed gradients */
+
+enum {
+  PS_OK = 0,
+  PS_ERR_ARG = -1,         /* null pointer, W outside [1, PS_MAX_W], numel <= 0, non-finite scalar */
+  PS_ERR_BAD_JOB = -2,     /* unknown or unregistered job id */
+  PS_ERR_BAD_BLOCK = -3,   /* block id outside the job */
+  PS_ERR_BAD_WORKER = -4,  /* worker outside [0, W) */
+  PS_ERR_DUP_PUSH = -5,    /* this worker already pushed this block in this round */
+  PS_ERR_NOT_READY = -6,   /* a listed block has not received all W pushes */
+  PS_ERR_DUP_BLOCK = -7,   /* the same block appears twice in one list */
+  PS_ERR_ALIGN = -8,       /* pointer not aligned as required */
+  PS_ERR_NOMEM = -9,       /* arena exhausted, or a host/device allocation failed */
+  PS_ERR_NO_DEVICE = -10,  /* the context was created without an arena (planning only) */
+  PS_ERR_HIP = -11,        /* a HIP runtime call failed; see ps_last_error */
+  PS_ERR_CAPACITY = -12    /* an output array is too small; the needed count is reported */
+};
+
+enum {
+  PS_FLAG_FP_CONTRACT = 1u /* use fused multiply-add in the update (not bit-exact with
+                              the separately rounded definition; error <= 1e-6 relative) */
+};
+
+typedef struct ps_ctx ps_ctx;
+typedef int32_t ps_job_t;
+
+typedef struct ps_config {
+  uint64_t max_block_bytes;   /* 0 = PS_DEFAULT_BLOCK_BYTES; must be a multiple of 256 */
+  uint32_t small_block_elems; /* blocks of at most this many values take the small-block
+                                 path; 0 = PS_DEFAULT_SMALL_ELEMS; at most 4096 */
+  uint32_t flags;             /* PS_FLAG_* */
+  void* arena_dev;            /* device memory for the master copies, 256-byte aligned,
+                                 owned by the caller, must outlive the context.
+                                 NULL = planning context: layouts, push state and wave
+                                 packing work, anything touching the device returns
+                                 PS_ERR_NO_DEVICE */
+  uint64_t arena_bytes;
+} ps_config;
+
+typedef struct ps_block_ref {
+  ps_job_t job;
+  int32_t block;
+} ps_block_ref;
+
+typedef struct ps_block_info {
+  int32_t layer;          /* index of the layer this block is a slice of */
+  int32_t W;              /* workers of the job */
+  int64_t layer_offset;   /* first element of the block inside its layer */
+  int64_t numel;          /* elements in the block */
+  int64_t flat_offset;    /* first element of the block inside the job's flat layout
+                             (every layer starts on a 256-byte boundary; a layer's blocks
+                             are contiguous).  Parameters, momentum and, by convention of
+                             ps_push_flat, a worker's gradient buffer share this layout. */
+  int64_t round;          /* aggregations applied to this block so far */
+  uint32_t push_mask;     /* bit w set = worker w has pushed for the current round */
+  uint32_t small_path;    /* 1 if the block takes the small-block kernel */
+} ps_block_info;
+
+typedef struct ps_block_stats {
+  double grad_norm2;      /* sum_i S_i^2 of the block's last aggregation */
+  int64_t round;          /* round that value belongs to (0 = never aggregated) */
+} ps_block_stats;
+
+typedef struct ps_wave_stats {
+  int64_t n_blocks;        /* blocks in the list */
+  int64_t n_params;        /* sum of their numel */
+  int64_t n_large_tiles;   /* workgroups of the large-block kernel */
+  int64_t n_small_blocks;  /* blocks routed to the small-block kernel */
+  int64_t n_small_bins;    /* workgroups of the small-block kernel */
+  int64_t small_params;    /* parameters in small-path blocks */
+  uint64_t algorithmic_bytes; /* sum over blocks of (4 W + 16) * numel */
+} ps_wave_stats;
+
+/* --- life cycle ---------------------------------------------------------- */
+
+/* Create a context.  cfg is copied.  No device memory is allocated here except
+ * the library's own small tables, which grow on demand inside ps_aggregate.
+ * Errors: PS_ERR_ARG (bad cfg, misaligned arena, small_block_elems > 4096). */
+int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx);
+
+/* Destroy a context and free the library's own tables.  The caller must have
+ * synchronised every stream that was passed to this context.  NULL is allowed. */
+void ps_destroy(ps_ctx* ctx);
+
+/* Bytes of arena a job with these layers occupies (parameters + momentum, with
+ * alignment padding), so the caller can size the arena before ps_create. */
+int32_t ps_job_arena_bytes(const ps_config* cfg, const int64_t* layer_numel, int32_t n_layers,
+                           uint64_t* out_bytes);
+
+/* --- registration (the paper's job registration + per-tensor Init) -------- */
+
+/* Register a job: split every layer into blocks, carve parameter and momentum
+ * shards out of the arena, zero the momentum, and set the parameters from
+ * init_params (host array of n_layers DEVICE pointers, layer l holding
+ * layer_numel[l] floats; the array itself or single entries may be NULL = zeros).
+ * The copies are enqueued on stream.  *out_job receives the id, *out_n_blocks
+ * the number of blocks.  Errors: PS_ERR_ARG, PS_ERR_NOMEM, PS_ERR_HIP. */
+int32_t ps_register_job(ps_ctx* ctx, const int64_t* layer_numel, int32_t n_layers, int32_t W,
+                        float lr, float momentum, float wd, const float* const* init_params,
+                        void* stream, ps_job_t* out_job, int32_t* out_n_blocks);
+
+/* Forget a job.  Its arena space is reused only if it was the most recently
+ * registered live job (the arena is a stack).  Pending pushes are dropped. */
+int32_t ps_unregister_job(ps_ctx* ctx, ps_job_t job);
+
+/* Number of blocks / flat elements (with padding) of a job; negative = error. */
+int32_t ps_job_n_blocks(ps_ctx* ctx, ps_job_t job);
+int64_t ps_job_flat_numel(ps_ctx* ctx, ps_job_t job);
+
+int32_t ps_job_block_info(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_info* out);
+
+/* --- push (worker -> service) -------------------------------------------- */
+
+/* Record worker's gradient for (job, block) for the block's current round.
+ * grad_dev: DEVICE pointer to numel floats, 16-byte aligned, owned by the
+ * caller; it is read, never written, by the aggregation that consumes it and
+ * must stay valid and unchanged until that aggregation has completed on its
+ * stream.  No data is copied.  Errors: BAD_JOB, BAD_BLOCK, BAD_WORKER,
+ * DUP_PUSH, ALIGN, ARG (NULL). */
+int32_t ps_push(ps_ctx* ctx, ps_job_t job, int32_t block, int32_t worker, const float* grad_dev);
+
+/* Push every block of the job from one worker whose gradient buffer grad_flat_dev
+ * (DEVICE, 256-byte aligned, ps_job_flat_numel floats) uses the job's flat
+ * layout.  All-or-nothing: on error no block is marked. */
+int32_t ps_push_flat(ps_ctx* ctx, ps_job_t job, int32_t worker, const float* grad_flat_dev);
+
+/* --- wave packing ---------------------------------------------------------- */
+
+/* Build the block list of one wave in which each listed job contributes one
+ * round.  Within a job, blocks come in back-propagation arrival order (last
+ * registered layer first, ascending offset inside a layer: Section 2.1).  Jobs
+ * are interleaved by fractional position: the k-th of n blocks of a job sits at
+ * (k + 1/2)/n; ascending position, ties to the job listed first.  Writes at most
+ * cap entries to out (host) and the total to *out_n; PS_ERR_CAPACITY if
+ * cap is too small (then *out_n is still the needed count).  A job listed twice
+ * is PS_ERR_DUP_BLOCK. */
+int32_t ps_pack_wave(ps_ctx* ctx, const ps_job_t* jobs, int32_t n_jobs, ps_block_ref* out,
+                     int64_t cap, int64_t* out_n);
+
+/* Validate a block list exactly as ps_aggregate would, and report how it would
+ * be laid out on the GPU.  Changes no state, touches no device. */
+int32_t ps_plan_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, ps_wave_stats* out);
+
+/* --- aggregate (the hot path) --------------------------------------------- */
+
+/* Aggregate every block of block_list (host array of n entries): sum the W
+ * pushed gradients in worker order and apply the update to the block's
+ * parameter and momentum shards, on stream.  All-or-nothing: the whole list is
+ * validated first (BAD_JOB, BAD_BLOCK, NOT_READY, DUP_BLOCK) and nothing is
+ * launched or changed on error.  On success every listed block's push mask is
+ * cleared and its round advances by one.  n = 0 is a no-op. */
+int32_t ps_aggregate(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, void* stream);
+
+/* --- pull (service -> worker) and inspection ------------------------------- */
+
+/* Borrowed DEVICE pointers to the block's parameters / momentum.  They stay
+ * valid until the job is unregistered; their contents are those of the last
+ * aggregation enqueued for the block, in stream order. */
+int32_t ps_pull(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_param_dev,
+                int64_t* out_numel);
+int32_t ps_pull_momentum(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_mom_dev,
+                         int64_t* out_numel);
+
+/* Base DEVICE pointers of the job's flat parameter and momentum arrays
+ * (ps_job_flat_numel floats each; block b starts at flat_offset). */
+int32_t ps_pull_flat(ps_ctx* ctx, ps_job_t job, const float** out_param_dev,
+                     const float** out_mom_dev, int64_t* out_flat_numel);
+
+/* Telemetry of a block's last aggregation.  The value is written by the GPU
+ * into host-visible memory at the end of the wave: the caller must have
+ * synchronised the wave's stream before reading. */
+int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* out);
+
+/* --- diagnostics ----------------------------------------------------------- */
+
+/* Static, never NULL. */
+const char* ps_strerror(int32_t status);
+/* Text of the last HIP failure seen by this context ("" if none).  Valid until
+ * the next call on the context. */
+const char* ps_last_error(ps_ctx* ctx);
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t ps_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_H_ */

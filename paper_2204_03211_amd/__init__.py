@@ -1,0 +1,15 @@
+"""GPU-resident parameter service for MI355X: model aggregation (sum of the
+workers' gradient pushes + momentum-SGD update of the master copy) as HIP
+kernels behind a C ABI.  See include/ps.h for the boundary."""
+from .binding import (  # noqa: F401
+    FLAG_FP_CONTRACT,
+    PS_MAX_W,
+    BlockInfo,
+    BlockRef,
+    BlockStats,
+    ParameterService,
+    PsError,
+    WaveList,
+    WaveStats,
+    load_library,
+)

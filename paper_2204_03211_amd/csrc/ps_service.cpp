@@ -1,0 +1,619 @@
+// Host side of the parameter service: job registry, block-descriptor table,
+// push state, wave packer and wave planner, behind the C ABI of ps.h.
+//
+// The paper's agent keeps a table from (job, tensor) to the server that owns the
+// tensor (Section 3.1; Appendix A); here every block lives on the one GPU and the
+// table maps (job, block) to its parameter / momentum shards in the arena.  The
+// paper's server runs the aggregations of several jobs in one cycle (Section
+// 3.3); here that is one ps_aggregate call over a list of blocks.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ps.h"
+#include "ps_internal.h"
+
+namespace {
+
+constexpr uint64_t kAlignElems = PS_ALIGN_BYTES / 4;
+
+inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+struct Block {
+  int32_t layer;
+  int64_t layer_off;
+  int64_t numel;
+  int64_t flat_off;
+  int64_t round = 0;
+  uint32_t mask = 0;
+  uint64_t wave_stamp = 0;  // id of the last list that named this block (duplicate check)
+  const float* grad[PS_MAX_W];
+};
+
+struct Job {
+  bool live = false;
+  int32_t W = 0;
+  float lr = 0, mu = 0, wd = 0;
+  uint32_t full_mask = 0;
+  std::vector<int64_t> layer_numel;
+  std::vector<Block> blocks;
+  std::vector<int32_t> arrival;  // block ids, last layer first
+  int64_t flat_numel = 0;        // elements, padded
+  uint64_t arena_off = 0;        // bytes from arena base: [p flat][v flat]
+  uint64_t arena_bytes = 0;
+  float* p = nullptr;
+  float* v = nullptr;
+  double* stat = nullptr;        // host-visible, one double per block
+  int64_t* stat_round = nullptr; // host only
+};
+
+// Device + pinned-host buffers for the tables of one in-flight wave.
+struct Slot {
+  char* host = nullptr;
+  char* dev = nullptr;
+  size_t host_cap = 0, dev_cap = 0;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+};
+constexpr int kSlots = 4;
+
+struct Plan {
+  std::vector<PsBlockDesc> desc;
+  std::vector<const float*> gptr;
+  std::vector<PsTile> tiles;
+  std::vector<PsSmallEntry> small_entries;
+  std::vector<PsBin> bins;
+  std::vector<uint32_t> large_blocks;
+  ps_wave_stats stats{};
+};
+
+}  // namespace
+
+struct ps_ctx {
+  std::mutex mu;
+  ps_config cfg{};
+  int64_t cap_elems = 0;
+  std::vector<Job> jobs;
+  uint64_t arena_top = 0;
+  uint64_t wave_counter = 0;
+  Slot slots[kSlots];
+  int next_slot = 0;
+  Plan plan;
+  std::string last_error;
+};
+
+namespace {
+
+int32_t normalise_config(const ps_config* in, ps_config* out) {
+  if (!in) return PS_ERR_ARG;
+  *out = *in;
+  if (out->max_block_bytes == 0) out->max_block_bytes = PS_DEFAULT_BLOCK_BYTES;
+  if (out->small_block_elems == 0) out->small_block_elems = PS_DEFAULT_SMALL_ELEMS;
+  if (out->max_block_bytes % PS_ALIGN_BYTES != 0) return PS_ERR_ARG;
+  if (out->max_block_bytes / 4 > 0xFFFFFFF0ull) return PS_ERR_ARG;  // block numel is 32-bit on the GPU
+  if (out->small_block_elems > PS_BIN_MAX_QUADS * 2) return PS_ERR_ARG;
+  if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
+  if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
+  return PS_OK;
+}
+
+// Flat layout of a job: every layer starts at a multiple of 64 elements.
+int32_t layout_layers(const int64_t* layer_numel, int32_t n_layers, int64_t cap_elems,
+                      std::vector<Block>* blocks, int64_t* flat_numel) {
+  if (!layer_numel || n_layers <= 0) return PS_ERR_ARG;
+  int64_t flat = 0;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const int64_t n = layer_numel[l];
+    if (n <= 0 || n > (int64_t(1) << 40)) return PS_ERR_ARG;
+    for (int64_t off = 0; off < n; off += cap_elems) {
+      if (blocks) {
+        Block b{};
+        b.layer = l;
+        b.layer_off = off;
+        b.numel = (n - off < cap_elems) ? n - off : cap_elems;
+        b.flat_off = flat + off;
+        blocks->push_back(b);
+      }
+    }
+    flat = (int64_t)round_up((uint64_t)(flat + n), kAlignElems);
+  }
+  *flat_numel = flat;
+  return PS_OK;
+}
+
+Job* find_job(ps_ctx* c, ps_job_t job) {
+  if (job < 0 || (size_t)job >= c->jobs.size() || !c->jobs[job].live) return nullptr;
+  return &c->jobs[job];
+}
+
+int32_t hip_fail(ps_ctx* c, hipError_t e, const char* what) {
+  c->last_error = std::string(what) + ": " + hipGetErrorString(e);
+  return PS_ERR_HIP;
+}
+#define PS_HIP(c, call)                                  \
+  do {                                                   \
+    hipError_t e_ = (call);                              \
+    if (e_ != hipSuccess) return hip_fail(c, e_, #call); \
+  } while (0)
+
+// Validate a block list and lay out the tables of its wave in c->plan.
+// Changes nothing but c->plan, c->wave_counter and the blocks' duplicate stamps.
+int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pushes) {
+  if (n < 0 || (n > 0 && !list)) return PS_ERR_ARG;
+  if (n > 0x7FFFFFF0ll) return PS_ERR_ARG;
+  Plan& P = c->plan;
+  P.desc.clear(); P.gptr.clear(); P.tiles.clear(); P.small_entries.clear();
+  P.bins.clear(); P.large_blocks.clear();
+  P.stats = ps_wave_stats{};
+  const uint64_t stamp = ++c->wave_counter;
+  const uint32_t small_max = c->cfg.small_block_elems;
+
+  // pass 1: validation only, so that an error leaves no trace
+  for (int64_t i = 0; i < n; ++i) {
+    Job* j = find_job(c, list[i].job);
+    if (!j) return PS_ERR_BAD_JOB;
+    if (list[i].block < 0 || (size_t)list[i].block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+    Block& b = j->blocks[list[i].block];
+    if (b.wave_stamp == stamp) return PS_ERR_DUP_BLOCK;
+    b.wave_stamp = stamp;
+    if (need_pushes && b.mask != j->full_mask) return PS_ERR_NOT_READY;
+  }
+
+  P.desc.reserve(n);
+  PsBin bin{0, 0, 0, 0};
+  auto close_bin = [&]() {
+    if (bin.count) P.bins.push_back(bin);
+    bin = PsBin{(uint32_t)P.small_entries.size(), 0, 0, 0};
+  };
+  for (int64_t i = 0; i < n; ++i) {
+    Job& j = c->jobs[list[i].job];
+    Block& b = j.blocks[list[i].block];
+    PsBlockDesc d{};
+    d.p = j.p ? j.p + b.flat_off : nullptr;
+    d.v = j.v ? j.v + b.flat_off : nullptr;
+    d.stat = j.stat ? j.stat + list[i].block : nullptr;
+    d.gofs = (uint32_t)P.gptr.size();
+    d.n = (uint32_t)b.numel;
+    d.W = (uint32_t)j.W;
+    d.lr = j.lr; d.mu = j.mu; d.wd = j.wd;
+    for (int32_t w = 0; w < j.W; ++w) P.gptr.push_back((b.mask >> w) & 1u ? b.grad[w] : nullptr);
+    const uint32_t di = (uint32_t)P.desc.size();
+    if (d.n <= small_max) {
+      const uint32_t q = (d.n + 3) / 4;
+      if (bin.count == PS_BIN_MAX_BLOCKS || bin.quads + q > PS_BIN_MAX_QUADS) close_bin();
+      P.small_entries.push_back(PsSmallEntry{di, bin.quads});
+      bin.count += 1;
+      bin.quads += q;
+      P.stats.n_small_blocks += 1;
+      P.stats.small_params += d.n;
+    } else {
+      d.tile0 = (uint32_t)P.tiles.size();
+      d.ntiles = (d.n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
+      for (uint32_t t = 0; t < d.ntiles; ++t) P.tiles.push_back(PsTile{di, t * PS_TILE_ELEMS});
+      P.large_blocks.push_back(di);
+    }
+    P.desc.push_back(d);
+    P.stats.n_params += d.n;
+    P.stats.algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
+  }
+  close_bin();
+  P.stats.n_blocks = n;
+  P.stats.n_large_tiles = (int64_t)P.tiles.size();
+  P.stats.n_small_bins = (int64_t)P.bins.size();
+  return PS_OK;
+}
+
+int32_t slot_reserve(ps_ctx* c, Slot& s, size_t host_bytes, size_t dev_bytes) {
+  if (s.in_flight) {
+    PS_HIP(c, hipEventSynchronize(s.done));
+    s.in_flight = false;
+  }
+  if (!s.done) PS_HIP(c, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+  if (host_bytes > s.host_cap) {
+    if (s.host) PS_HIP(c, hipHostFree(s.host));
+    s.host = nullptr; s.host_cap = 0;
+    const size_t cap = round_up(host_bytes + host_bytes / 2, 4096);
+    PS_HIP(c, hipHostMalloc((void**)&s.host, cap, hipHostMallocDefault));
+    s.host_cap = cap;
+  }
+  if (dev_bytes > s.dev_cap) {
+    if (s.dev) PS_HIP(c, hipFree(s.dev));
+    s.dev = nullptr; s.dev_cap = 0;
+    const size_t cap = round_up(dev_bytes + dev_bytes / 2, 4096);
+    PS_HIP(c, hipMalloc((void**)&s.dev, cap));
+    s.dev_cap = cap;
+  }
+  return PS_OK;
+}
+
+template <class T>
+size_t place(size_t* cursor, size_t count) {
+  const size_t at = round_up(*cursor, 256);
+  *cursor = at + count * sizeof(T);
+  return at;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ps_version(void) { return 100; }
+
+const char* ps_strerror(int32_t s) {
+  switch (s) {
+    case PS_OK: return "ok";
+    case PS_ERR_ARG: return "invalid argument";
+    case PS_ERR_BAD_JOB: return "unknown job";
+    case PS_ERR_BAD_BLOCK: return "block id outside the job";
+    case PS_ERR_BAD_WORKER: return "worker outside [0, W)";
+    case PS_ERR_DUP_PUSH: return "worker already pushed this block in this round";
+    case PS_ERR_NOT_READY: return "block has not received all W pushes";
+    case PS_ERR_DUP_BLOCK: return "block listed twice";
+    case PS_ERR_ALIGN: return "pointer not aligned as required";
+    case PS_ERR_NOMEM: return "out of arena or memory";
+    case PS_ERR_NO_DEVICE: return "planning context: no device arena";
+    case PS_ERR_HIP: return "HIP runtime call failed";
+    case PS_ERR_CAPACITY: return "output array too small";
+    default: return "unknown status";
+  }
+}
+
+const char* ps_last_error(ps_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+
+int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) {
+  if (!out_ctx) return PS_ERR_ARG;
+  *out_ctx = nullptr;
+  ps_config n{};
+  const int32_t st = normalise_config(cfg, &n);
+  if (st != PS_OK) return st;
+  ps_ctx* c = new (std::nothrow) ps_ctx();
+  if (!c) return PS_ERR_NOMEM;
+  c->cfg = n;
+  c->cap_elems = (int64_t)(n.max_block_bytes / 4);
+  *out_ctx = c;
+  return PS_OK;
+}
+
+void ps_destroy(ps_ctx* c) {
+  if (!c) return;
+  for (Slot& s : c->slots) {
+    if (s.in_flight) (void)hipEventSynchronize(s.done);
+    if (s.done) (void)hipEventDestroy(s.done);
+    if (s.host) (void)hipHostFree(s.host);
+    if (s.dev) (void)hipFree(s.dev);
+  }
+  for (Job& j : c->jobs) {
+    if (j.stat && c->cfg.arena_dev) (void)hipHostFree(j.stat);
+    else delete[] j.stat;
+    delete[] j.stat_round;
+  }
+  delete c;
+}
+
+int32_t ps_job_arena_bytes(const ps_config* cfg, const int64_t* layer_numel, int32_t n_layers,
+                           uint64_t* out_bytes) {
+  if (!out_bytes) return PS_ERR_ARG;
+  ps_config n{};
+  int32_t st = normalise_config(cfg, &n);
+  if (st != PS_OK) return st;
+  int64_t flat = 0;
+  st = layout_layers(layer_numel, n_layers, (int64_t)(n.max_block_bytes / 4), nullptr, &flat);
+  if (st != PS_OK) return st;
+  *out_bytes = (uint64_t)flat * 4 * 2;
+  return PS_OK;
+}
+
+int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
+                        float momentum, float wd, const float* const* init_params, void* stream,
+                        ps_job_t* out_job, int32_t* out_n_blocks) {
+  if (!c || !out_job) return PS_ERR_ARG;
+  if (W < 1 || W > PS_MAX_W) return PS_ERR_ARG;
+  if (!std::isfinite(lr) || !std::isfinite(momentum) || !std::isfinite(wd)) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job j;
+  int32_t st = layout_layers(layer_numel, n_layers, c->cap_elems, &j.blocks, &j.flat_numel);
+  if (st != PS_OK) return st;
+  if (j.blocks.size() > 0x7FFFFFF0u) return PS_ERR_ARG;
+  j.W = W; j.lr = lr; j.mu = momentum; j.wd = wd;
+  j.full_mask = (W == 32) ? 0xFFFFFFFFu : ((1u << W) - 1u);
+  j.layer_numel.assign(layer_numel, layer_numel + n_layers);
+  // arrival order: last registered layer first, ascending offset inside a layer
+  {
+    const int32_t nb = (int32_t)j.blocks.size();
+    j.arrival.reserve(nb);
+    int32_t end = nb;
+    while (end > 0) {
+      int32_t begin = end;
+      const int32_t layer = j.blocks[end - 1].layer;
+      while (begin > 0 && j.blocks[begin - 1].layer == layer) --begin;
+      for (int32_t b = begin; b < end; ++b) j.arrival.push_back(b);
+      end = begin;
+    }
+  }
+  j.arena_bytes = (uint64_t)j.flat_numel * 4 * 2;
+  j.arena_off = c->arena_top;
+  const size_t nb = j.blocks.size();
+  const bool device = c->cfg.arena_dev != nullptr;
+  if (device) {
+    if (j.arena_off + j.arena_bytes > c->cfg.arena_bytes) return PS_ERR_NOMEM;
+    char* base = static_cast<char*>(c->cfg.arena_dev) + j.arena_off;
+    j.p = reinterpret_cast<float*>(base);
+    j.v = j.p + j.flat_numel;
+    PS_HIP(c, hipHostMalloc((void**)&j.stat, nb * sizeof(double), hipHostMallocDefault));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemsetAsync(j.p, 0, j.arena_bytes, s);  // parameters' padding and all momentum
+    if (e == hipSuccess && init_params) {
+      int64_t flat = 0;
+      for (int32_t l = 0; l < n_layers && e == hipSuccess; ++l) {
+        if (init_params[l])
+          e = hipMemcpyAsync(j.p + flat, init_params[l], (size_t)layer_numel[l] * 4,
+                             hipMemcpyDeviceToDevice, s);
+        flat = (int64_t)round_up((uint64_t)(flat + layer_numel[l]), kAlignElems);
+      }
+    }
+    if (e != hipSuccess) {
+      (void)hipHostFree(j.stat);
+      return hip_fail(c, e, "initialising the job's shards");
+    }
+  } else {
+    j.stat = new (std::nothrow) double[nb];
+    if (!j.stat) return PS_ERR_NOMEM;
+  }
+  j.stat_round = new (std::nothrow) int64_t[nb];
+  if (!j.stat_round) return PS_ERR_NOMEM;
+  for (size_t b = 0; b < nb; ++b) { j.stat[b] = 0.0; j.stat_round[b] = 0; }
+  j.live = true;
+  c->arena_top = round_up(j.arena_off + j.arena_bytes, PS_ALIGN_BYTES);
+  c->jobs.push_back(std::move(j));
+  *out_job = (ps_job_t)(c->jobs.size() - 1);
+  if (out_n_blocks) *out_n_blocks = (int32_t)nb;
+  return PS_OK;
+}
+
+int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  j->live = false;
+  if (j->stat && c->cfg.arena_dev) (void)hipHostFree(j->stat);
+  else delete[] j->stat;
+  delete[] j->stat_round;
+  j->stat = nullptr; j->stat_round = nullptr;
+  j->blocks.clear(); j->blocks.shrink_to_fit();
+  // pop the arena stack past every dead job on top
+  uint64_t top = 0;
+  for (const Job& o : c->jobs)
+    if (o.live) top = std::max<uint64_t>(top, round_up(o.arena_off + o.arena_bytes, PS_ALIGN_BYTES));
+  c->arena_top = top;
+  return PS_OK;
+}
+
+int32_t ps_job_n_blocks(ps_ctx* c, ps_job_t job) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  return j ? (int32_t)j->blocks.size() : PS_ERR_BAD_JOB;
+}
+
+int64_t ps_job_flat_numel(ps_ctx* c, ps_job_t job) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  return j ? j->flat_numel : (int64_t)PS_ERR_BAD_JOB;
+}
+
+int32_t ps_job_block_info(ps_ctx* c, ps_job_t job, int32_t block, ps_block_info* out) {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  const Block& b = j->blocks[block];
+  out->layer = b.layer;
+  out->W = j->W;
+  out->layer_offset = b.layer_off;
+  out->numel = b.numel;
+  out->flat_offset = b.flat_off;
+  out->round = b.round;
+  out->push_mask = b.mask;
+  out->small_path = b.numel <= (int64_t)c->cfg.small_block_elems ? 1u : 0u;
+  return PS_OK;
+}
+
+int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const float* grad_dev) {
+  if (!c || !grad_dev) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  if (worker < 0 || worker >= j->W) return PS_ERR_BAD_WORKER;
+  if (reinterpret_cast<uintptr_t>(grad_dev) % PS_GRAD_ALIGN_BYTES) return PS_ERR_ALIGN;
+  Block& b = j->blocks[block];
+  if ((b.mask >> worker) & 1u) return PS_ERR_DUP_PUSH;
+  b.grad[worker] = grad_dev;
+  b.mask |= 1u << worker;
+  return PS_OK;
+}
+
+int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_flat_dev) {
+  if (!c || !grad_flat_dev) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (worker < 0 || worker >= j->W) return PS_ERR_BAD_WORKER;
+  if (reinterpret_cast<uintptr_t>(grad_flat_dev) % PS_ALIGN_BYTES) return PS_ERR_ALIGN;
+  const uint32_t bit = 1u << worker;
+  for (const Block& b : j->blocks)
+    if (b.mask & bit) return PS_ERR_DUP_PUSH;
+  for (Block& b : j->blocks) {
+    b.grad[worker] = grad_flat_dev + b.flat_off;
+    b.mask |= bit;
+  }
+  return PS_OK;
+}
+
+int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_ref* out, int64_t cap,
+                     int64_t* out_n) {
+  if (!c || !out_n || n_jobs < 0 || (n_jobs > 0 && !jobs) || cap < 0 || (cap > 0 && !out))
+    return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  int64_t total = 0;
+  for (int32_t a = 0; a < n_jobs; ++a) {
+    Job* j = find_job(c, jobs[a]);
+    if (!j) return PS_ERR_BAD_JOB;
+    for (int32_t b = 0; b < a; ++b)
+      if (jobs[b] == jobs[a]) return PS_ERR_DUP_BLOCK;
+    total += (int64_t)j->arrival.size();
+  }
+  *out_n = total;
+  if (total > cap) return PS_ERR_CAPACITY;
+  // k-way merge by position (2k+1)/(2n), compared exactly by cross-multiplication
+  std::vector<int64_t> head(n_jobs, 0);
+  for (int64_t t = 0; t < total; ++t) {
+    int32_t best = -1;
+    int64_t bk = 0, bn = 1;
+    for (int32_t a = 0; a < n_jobs; ++a) {
+      const int64_t n = (int64_t)c->jobs[jobs[a]].arrival.size();
+      const int64_t k = head[a];
+      if (k >= n) continue;
+      if (best < 0 || (unsigned __int128)(2 * k + 1) * (uint64_t)bn <
+                          (unsigned __int128)(2 * bk + 1) * (uint64_t)n) {
+        best = a; bk = k; bn = n;
+      }
+    }
+    out[t].job = jobs[best];
+    out[t].block = c->jobs[jobs[best]].arrival[bk];
+    head[best] = bk + 1;
+  }
+  return PS_OK;
+}
+
+int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_stats* out) {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  const int32_t st = build_plan(c, list, n, /*need_pushes=*/true);
+  if (st != PS_OK) return st;
+  *out = c->plan.stats;
+  return PS_OK;
+}
+
+int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  int32_t st = build_plan(c, list, n, /*need_pushes=*/true);
+  if (st != PS_OK) return st;
+  if (n == 0) return PS_OK;
+  if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
+  Plan& P = c->plan;
+
+  size_t cur = 0;
+  const size_t o_desc = place<PsBlockDesc>(&cur, P.desc.size());
+  const size_t o_gptr = place<const float*>(&cur, P.gptr.size());
+  const size_t o_tiles = place<PsTile>(&cur, P.tiles.size());
+  const size_t o_small = place<PsSmallEntry>(&cur, P.small_entries.size());
+  const size_t o_bins = place<PsBin>(&cur, P.bins.size());
+  const size_t o_large = place<uint32_t>(&cur, P.large_blocks.size());
+  const size_t upload = cur;
+  const size_t o_part = place<double>(&cur, P.tiles.size());
+  const size_t dev_total = cur;
+
+  Slot& s = c->slots[c->next_slot];
+  c->next_slot = (c->next_slot + 1) % kSlots;
+  st = slot_reserve(c, s, upload, dev_total);
+  if (st != PS_OK) return st;
+  auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(s.host + at, src, bytes); };
+  put(o_desc, P.desc.data(), P.desc.size() * sizeof(PsBlockDesc));
+  put(o_gptr, P.gptr.data(), P.gptr.size() * sizeof(const float*));
+  put(o_tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
+  put(o_small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
+  put(o_bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
+  put(o_large, P.large_blocks.data(), P.large_blocks.size() * sizeof(uint32_t));
+
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
+  PsWaveTables t{};
+  t.desc = reinterpret_cast<const PsBlockDesc*>(s.dev + o_desc);
+  t.gptr = reinterpret_cast<const float* const*>(s.dev + o_gptr);
+  t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
+  t.n_tiles = (uint32_t)P.tiles.size();
+  t.tile_part = reinterpret_cast<double*>(s.dev + o_part);
+  t.small_entries = reinterpret_cast<const PsSmallEntry*>(s.dev + o_small);
+  t.bins = reinterpret_cast<const PsBin*>(s.dev + o_bins);
+  t.n_bins = (uint32_t)P.bins.size();
+  t.large_blocks = reinterpret_cast<const uint32_t*>(s.dev + o_large);
+  t.n_large_blocks = (uint32_t)P.large_blocks.size();
+  t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
+  const int le = ps_launch_wave(t, stream);
+  if (le != 0) return hip_fail(c, (hipError_t)le, "launching the wave");
+  PS_HIP(c, hipEventRecord(s.done, hs));
+  s.in_flight = true;
+
+  // the wave is enqueued: consume the pushes
+  for (int64_t i = 0; i < n; ++i) {
+    Job& j = c->jobs[list[i].job];
+    Block& b = j.blocks[list[i].block];
+    b.mask = 0;
+    b.round += 1;
+    j.stat_round[list[i].block] = b.round;
+  }
+  return PS_OK;
+}
+
+int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_dev, int64_t* out_numel) {
+  if (!c || !out_param_dev) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  if (!j->p) return PS_ERR_NO_DEVICE;
+  *out_param_dev = j->p + j->blocks[block].flat_off;
+  if (out_numel) *out_numel = j->blocks[block].numel;
+  return PS_OK;
+}
+
+int32_t ps_pull_momentum(ps_ctx* c, ps_job_t job, int32_t block, const float** out_mom_dev,
+                         int64_t* out_numel) {
+  if (!c || !out_mom_dev) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  if (!j->v) return PS_ERR_NO_DEVICE;
+  *out_mom_dev = j->v + j->blocks[block].flat_off;
+  if (out_numel) *out_numel = j->blocks[block].numel;
+  return PS_OK;
+}
+
+int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const float** out_mom_dev,
+                     int64_t* out_flat_numel) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (!j->p) return PS_ERR_NO_DEVICE;
+  if (out_param_dev) *out_param_dev = j->p;
+  if (out_mom_dev) *out_mom_dev = j->v;
+  if (out_flat_numel) *out_flat_numel = j->flat_numel;
+  return PS_OK;
+}
+
+int32_t ps_telemetry(ps_ctx* c, ps_job_t job, int32_t block, ps_block_stats* out) {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  out->grad_norm2 = reinterpret_cast<volatile double*>(j->stat)[block];
+  out->round = j->stat_round[block];
+  return PS_OK;
+}
+
+}  // extern "C"

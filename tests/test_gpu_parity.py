@@ -1,0 +1,254 @@
+"""Parity of the HIP aggregation path with the CPU oracle, through the C ABI.
+
+Bar: parameters and momentum bit-exact (the default mode rounds every
+operation separately, as the oracle does); telemetry within 1e-12 relative
+(both sides accumulate exact products in binary64, in different orders)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from harness import GpuService, OracleService, layer_values
+from paper_2204_03211_amd import FLAG_FP_CONTRACT, PsError, WaveList
+
+pytestmark = pytest.mark.gpu
+
+F = np.float32
+
+
+def spec(layers, W, lr=0.1, mu=0.9, wd=1e-4, gstd=1e-2, pstd=0.05, model="synthetic"):
+    return wl.JobSpec(model, tuple(layers), W, lr, mu, wd, gstd, pstd)
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=F).view(np.uint32)
+
+
+def assert_state_equal(gpu: GpuService, orc: OracleService, what=""):
+    torch.cuda.synchronize()
+    for ji, s in enumerate(gpu.specs):
+        for l in range(len(s.layer_numel)):
+            gp = gpu.layer_param(ji, l).cpu().numpy()
+            gv = gpu.layer_momentum(ji, l).cpu().numpy()
+            bad_p = np.flatnonzero(bits(gp) != bits(orc.jobs[ji].p[l]))
+            bad_v = np.flatnonzero(bits(gv) != bits(orc.jobs[ji].v[l]))
+            assert bad_p.size == 0 and bad_v.size == 0, (
+                f"{what} job {ji} layer {l} (numel {s.layer_numel[l]}, W {s.W}): "
+                f"{bad_p.size} param / {bad_v.size} momentum mismatches, first at "
+                f"{bad_p[:3]} / {bad_v[:3]}")
+
+
+def assert_telemetry_close(gpu: GpuService, orc: OracleService, rel=1e-12):
+    torch.cuda.synchronize()
+    for ji in range(len(gpu.specs)):
+        oj = orc.jobs[ji]
+        for b in range(len(oj.blocks)):
+            st = gpu.svc.telemetry(gpu.jobs[ji], b)
+            assert st.round == oj.round[b]
+            assert st.grad_norm2 == pytest.approx(oj.norm2[b], rel=rel, abs=0.0), (ji, b)
+
+
+def run_both(orc_mod, specs, seed, rounds=3, **kw):
+    gpu = GpuService(specs, seed, **kw)
+    cap = (kw.get("max_block_bytes") or (4 << 20)) // 4
+    orc = OracleService(orc_mod, specs, seed, cap_elems=cap)
+    for r in range(rounds):
+        gpu.fill_grads(r)
+        gpu.step()
+        orc.step(r)
+        assert_state_equal(gpu, orc, f"round {r}")
+        assert_telemetry_close(gpu, orc)
+    return gpu, orc
+
+
+def test_generator_same_bits_on_gpu_and_cpu():
+    a = layer_values(3, "grad", (1, 2, 3, 4), 100_003, 1e-3, "cpu", start=17)
+    b = layer_values(3, "grad", (1, 2, 3, 4), 100_003, 1e-3, "cuda:0", start=17).cpu()
+    assert torch.equal(a, b)
+
+
+def test_small_config_mlp_three_rounds(orc):
+    """784-512-10 perceptron, 2 workers, 4 tensors as one block each, seed 0."""
+    s = wl.job_config("mlp")
+    gpu, o = run_both(orc, [s], seed=0, rounds=3)
+    assert len(gpu.blocks[0]) == 4
+    gpu.close()
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 8, 16, 17, 32])
+def test_ragged_sizes_every_worker_count(orc, W):
+    """Sizes around every boundary the kernels have: 16-byte quads (n % 4 != 0),
+    the small-path threshold (4096), the tile (4096) and several tiles plus a
+    ragged tail, and one-element tensors."""
+    layers = [1, 2, 3, 5, 63, 64, 65, 1000, 4095, 4096, 4097, 4099, 8191, 8192, 8193,
+              3 * 4096 + 1, 5 * 4096 + 1023, 10, 33278]
+    gpu, o = run_both(orc, [spec(layers, W)], seed=100 + W, rounds=3)
+    st = gpu.svc  # the list really used both paths
+    gpu.push_all()
+    ws = st.plan_wave(gpu.wave())
+    assert ws.n_small_blocks == 11 and ws.n_large_tiles > 0
+    gpu.close()
+
+
+def test_blocks_split_at_a_small_cap(orc):
+    """A 1 KiB block cap forces many blocks per layer; bits must not change
+    (block independence), and a layer's blocks are contiguous in the arena."""
+    layers = [10_000, 257, 70_001]
+    a, oa = run_both(orc, [spec(layers, 4)], seed=5, rounds=2, max_block_bytes=1024)
+    b, ob = run_both(orc, [spec(layers, 4)], seed=5, rounds=2)
+    assert len(a.blocks[0]) > 300 and len(b.blocks[0]) == 3
+    for l in range(3):
+        assert torch.equal(a.layer_param(0, l), b.layer_param(0, l))
+        assert torch.equal(a.layer_momentum(0, l), b.layer_momentum(0, l))
+    a.close(); b.close()
+
+
+def test_packed_multi_job_wave(orc):
+    """Several jobs of different W and hyper-parameters interleaved in one wave."""
+    specs = [
+        spec([40_000, 100, 4096 * 3, 7], 2, lr=0.1, mu=0.9, wd=1e-4),
+        spec([64, 64, 9000, 64, 64, 70_000], 16, lr=0.01, mu=0.5, wd=5e-4),
+        spec([12_345], 8, lr=0.05, mu=0.0, wd=0.0),
+        spec([333, 50_001, 2], 4, lr=1.0, mu=0.99, wd=0.1),
+        spec([5000, 5000], 3, lr=0.01, mu=0.9, wd=1e-4),
+    ]
+    gpu, o = run_both(orc, specs, seed=42, rounds=3, max_block_bytes=64 * 1024)
+    wave = gpu.wave().tolist()
+    assert wave == [(gpu.jobs[j], b) for j, b in orc.pack_wave(o.jobs)]
+    assert len({j for j, _ in wave[:6]}) >= 3          # jobs really are interleaved
+    gpu.close()
+
+
+def test_any_order_and_any_partition_of_a_wave(orc):
+    """Permuting the list, or cutting one wave into many calls, changes nothing."""
+    specs = [spec([30_000, 100, 4097], 4), spec([64, 20_000], 8)]
+    ref, _ = run_both(orc, specs, seed=9, rounds=2, max_block_bytes=16 * 1024)
+    alt = GpuService(specs, 9, max_block_bytes=16 * 1024)
+    rng = np.random.default_rng(0)
+    for r in range(2):
+        alt.fill_grads(r)
+        alt.push_all()
+        refs = alt.wave().tolist()
+        rng.shuffle(refs)
+        cuts = sorted(rng.choice(np.arange(1, len(refs)), size=3, replace=False))
+        for part in np.split(np.array(refs), cuts):
+            alt.svc.aggregate(WaveList([tuple(x) for x in part.tolist()]))
+    torch.cuda.synchronize()
+    for ji, s in enumerate(specs):
+        for l in range(len(s.layer_numel)):
+            assert torch.equal(ref.layer_param(ji, l), alt.layer_param(ji, l))
+            assert torch.equal(ref.layer_momentum(ji, l), alt.layer_momentum(ji, l))
+    ref.close(); alt.close()
+
+
+def test_special_values_denormals_and_signed_zero(orc):
+    """Hand-placed gradients: denormals, signed zeros, cancellation, the order
+    and no-fma cases of the oracle's pins -- pushed through both kernels."""
+    e = 2.0 ** -24
+    a, b = 1 + 2.0 ** -12, 1 + 2.0 ** -11
+    cases = [  # (g per worker (4), p, v)
+        ([1.0, e, e, -1.0], 0.0, 0.0),
+        ([-1.0, e, e, 1.0], 0.0, 0.0),
+        ([1e-45, 1e-45, -1e-45, 1e-40], 1e-39, -1e-41),
+        ([-0.0, -0.0, -0.0, -0.0], -0.0, -0.0),
+        ([0.0, 0.0, 0.0, -b], a, 0.0),
+        ([3e38, -3e38, 3e38, -3e38], 1.0, 1.0),
+        ([1.17549435e-38, -1.17549421e-38, 0.0, 0.0], 1e-30, 1e-38),
+    ]
+    for n_rep, lr, mu, wd in [(1, 1.0, 0.0, float(F(a))), (700, 1.0, 0.0, float(F(a))),
+                              (1500, 0.5, float(F(a)), 0.25)]:
+        n = len(cases) * n_rep      # 7 (small path, scalar tail) / 4900 / 10500 (large path)
+        s = spec([n], 4, lr=lr, mu=mu, wd=wd)
+        gpu = GpuService([s], 0)
+        o = orc.OracleJob((n,), 4, lr, mu, wd)
+        g = [np.tile(np.array([c[0][w] for c in cases], dtype=F), n_rep) for w in range(4)]
+        p0 = np.tile(np.array([c[1] for c in cases], dtype=F), n_rep)
+        v0 = np.tile(np.array([c[2] for c in cases], dtype=F), n_rep)
+        o.p[0][:] = p0
+        o.v[0][:] = v0
+        pf, vf = gpu.svc.pull_flat(gpu.jobs[0])
+        pf[:n].copy_(torch.from_numpy(p0))
+        vf[:n].copy_(torch.from_numpy(v0))
+        for w in range(4):
+            gpu.grads[0][w][:n].copy_(torch.from_numpy(g[w]))
+        for r in range(2):
+            gpu.step()
+            o.aggregate(0, g)
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(pf[:n].cpu().numpy()), bits(o.p[0])), (n, r)
+            assert np.array_equal(bits(vf[:n].cpu().numpy()), bits(o.v[0])), (n, r)
+        gpu.close()
+
+
+def test_contracted_mode_within_tolerance(orc):
+    """With fused multiply-add allowed the result may differ in the last place:
+    max |delta| / max(|oracle|, rms(oracle)) <= 1e-6 per block."""
+    layers = [50_000, 1000, 4097]
+    s = spec(layers, 8)
+    gpu = GpuService([s], 77, flags=FLAG_FP_CONTRACT)
+    o = OracleService(orc, [s], 77)
+    for r in range(3):
+        gpu.fill_grads(r)
+        gpu.step()
+        o.step(r)
+    torch.cuda.synchronize()
+    for l in range(len(layers)):
+        for got, want in ((gpu.layer_param(0, l).cpu().numpy(), o.jobs[0].p[l]),
+                          (gpu.layer_momentum(0, l).cpu().numpy(), o.jobs[0].v[l])):
+            rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+            rel = np.abs(got.astype(np.float64) - want) / np.maximum(np.abs(want), rms)
+            assert rel.max() <= 1e-6
+    gpu.close()
+
+
+def test_errors_and_state_machine_on_the_device():
+    s = spec([5000, 10], 2)
+    gpu = GpuService([s], 1)
+    svc, job = gpu.svc, gpu.jobs[0]
+    wave = gpu.wave()
+    with pytest.raises(PsError) as ei:
+        svc.aggregate(wave)
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    svc.push_flat(job, 0, gpu.grads[0][0])
+    with pytest.raises(PsError) as ei:
+        svc.aggregate(wave)                       # worker 1 missing: never a partial sum
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    p_before = gpu.layer_param(0, 0).clone()
+    svc.push_flat(job, 1, gpu.grads[0][1])
+    with pytest.raises(PsError) as ei:
+        svc.aggregate(WaveList(wave.tolist() + [wave.tolist()[0]]))
+    assert ei.value.name == "PS_ERR_DUP_BLOCK"
+    torch.cuda.synchronize()
+    assert torch.equal(p_before, gpu.layer_param(0, 0))   # failed calls launched nothing
+    assert svc.job_block_info(job, 0).round == 0
+    svc.aggregate(WaveList([]))                           # empty list: no-op
+    svc.aggregate(wave)
+    torch.cuda.synchronize()
+    info = svc.job_block_info(job, 0)
+    assert info.round == 1 and info.push_mask == 0
+    with pytest.raises(PsError) as ei:
+        svc.aggregate(wave)                               # pushes were consumed
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    assert svc.pull(job, 1).numel() == 10
+    gpu.close()
+
+
+@pytest.mark.parametrize("model", ["alexnet", "resnet50", "vgg16"])
+def test_full_size_single_job_configs(orc, model):
+    """The single-job configurations at full size, three rounds, every element
+    compared.  Gradients are generated on the GPU by the seeded generator and
+    copied to the host for the oracle."""
+    s = wl.job_config(model)
+    gpu = GpuService([s], 0)
+    o = OracleService(orc, [s], 0, gen_device="cuda:0")
+    wave = gpu.wave()
+    if model == "vgg16":                                   # pushed last layer first
+        first = gpu.svc.job_block_info(gpu.jobs[0], wave.tolist()[0][1])
+        assert first.layer == len(s.layer_numel) - 1
+    for r in range(3):
+        gpu.fill_grads(r)
+        gpu.step(wave)
+        o.step(r)
+    assert_state_equal(gpu, o, model)
+    assert_telemetry_close(gpu, o)
+    gpu.close()

@@ -1,0 +1,180 @@
+"""Host logic of the library on the CPU (planning context: no device is
+touched): block layout, wave packing, push state, validation, planning."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from paper_2204_03211_amd import ParameterService, PsError, WaveList, load_library
+from paper_2204_03211_amd.binding import Config
+
+CAP = 1 << 20
+FAKE = 256 * 4096   # a 256-byte aligned number standing in for a device address
+
+
+def reg(svc, layers, W=2):
+    return svc.register_job(layers, W, 0.1, 0.9, 1e-4)
+
+
+@pytest.mark.parametrize("model", ["mlp", "alexnet", "resnet50", "vgg16", "bert_base", "awd_lm"])
+def test_layout_matches_oracle_split(orc, model):
+    s = wl.job_config(model)
+    svc = ParameterService(None)
+    job, nb = reg(svc, s.layer_numel, s.W)
+    want = orc.split_layers(s.layer_numel, CAP)
+    assert nb == len(want) == svc.job_n_blocks(job)
+    flat = 0
+    prev_layer = -1
+    for b, (layer, off, n) in enumerate(want):
+        i = svc.job_block_info(job, b)
+        assert (i.layer, i.layer_offset, i.numel, i.W) == (layer, off, n, s.W)
+        if layer != prev_layer:
+            flat = -(-flat // 64) * 64            # each layer starts 256-byte aligned
+            layer_base, prev_layer = flat, layer
+            flat += s.layer_numel[layer]
+        assert i.flat_offset == layer_base + off and i.flat_offset % 4 == 0
+        assert i.small_path == (1 if n <= 4096 else 0)
+    assert svc.job_flat_numel(job) == -(-flat // 64) * 64
+    assert ParameterService.job_arena_bytes(s.layer_numel) == 8 * svc.job_flat_numel(job)
+
+
+def test_layout_random_caps_match_oracle(orc):
+    rng = np.random.default_rng(0)
+    for _ in range(30):
+        layers = [int(x) for x in rng.integers(1, 9000, size=rng.integers(1, 9))]
+        cap_bytes = int(rng.integers(1, 40)) * 256
+        svc = ParameterService(None, max_block_bytes=cap_bytes)
+        job, nb = reg(svc, layers)
+        want = orc.split_layers(layers, cap_bytes // 4)
+        got = [svc.job_block_info(job, b) for b in range(nb)]
+        assert [(i.layer, i.layer_offset, i.numel) for i in got] == want
+        ends = sorted((i.flat_offset, i.flat_offset + i.numel) for i in got)
+        assert all(a[1] <= b[0] for a, b in zip(ends, ends[1:]))    # shards never overlap
+
+
+def test_pack_wave_matches_oracle_on_the_twelve_job_wave(orc):
+    specs = wl.packed_wave_jobs(42)
+    svc = ParameterService(None)
+    jobs = [reg(svc, s.layer_numel, s.W)[0] for s in specs]
+    ojobs = []
+    for s in specs:
+        o = orc.OracleJob.__new__(orc.OracleJob)
+        o.blocks = orc.split_layers(s.layer_numel, CAP)
+        o.arrival = (lambda o=o: orc.arrival_order([b[0] for b in o.blocks]))
+        ojobs.append(o)
+    wave = svc.pack_wave(jobs)
+    assert wave.tolist() == [(jobs[j], b) for j, b in orc.pack_wave(ojobs)]
+    assert len(wave) == 1743
+    # a subset of jobs, listed in another order: ties follow the listing order
+    sub = [jobs[5], jobs[0], jobs[11]]
+    got = svc.pack_wave(sub).tolist()
+    want = [(sub[j], b) for j, b in orc.pack_wave([ojobs[5], ojobs[0], ojobs[11]])]
+    assert got == want
+
+
+def test_pack_wave_errors_and_capacity():
+    svc = ParameterService(None)
+    a, _ = reg(svc, [10, 5000])
+    L = load_library()
+    from paper_2204_03211_amd.binding import BlockRef
+    need = C.c_int64()
+    ja = (C.c_int32 * 2)(a, a)
+    out = (BlockRef * 1)()
+    assert L.ps_pack_wave(svc.ctx, ja, 1, out, 1, C.byref(need)) == -12 and need.value == 2
+    assert L.ps_pack_wave(svc.ctx, ja, 2, out, 1, C.byref(need)) == -7      # job listed twice
+    ja[1] = 99
+    assert L.ps_pack_wave(svc.ctx, ja, 2, out, 1, C.byref(need)) == -2
+    assert svc.pack_wave([]).tolist() == []
+
+
+def test_push_state_machine():
+    svc = ParameterService(None)
+    job, nb = reg(svc, [5000, 10], W=3)
+    cases = [
+        (lambda: svc.push(job, 0, 3, FAKE), "PS_ERR_BAD_WORKER"),
+        (lambda: svc.push(job, 0, -1, FAKE), "PS_ERR_BAD_WORKER"),
+        (lambda: svc.push(job, 2, 0, FAKE), "PS_ERR_BAD_BLOCK"),
+        (lambda: svc.push(job + 1, 0, 0, FAKE), "PS_ERR_BAD_JOB"),
+        (lambda: svc.push(job, 0, 0, FAKE + 4), "PS_ERR_ALIGN"),
+        (lambda: svc.push(job, 0, 0, 0), "PS_ERR_ARG"),
+        (lambda: svc.push_flat(job, 0, FAKE + 16), "PS_ERR_ALIGN"),
+    ]
+    for fn, name in cases:
+        with pytest.raises(PsError) as ei:
+            fn()
+        assert ei.value.name == name
+    svc.push(job, 0, 1, FAKE)
+    assert svc.job_block_info(job, 0).push_mask == 0b010
+    with pytest.raises(PsError) as ei:
+        svc.push(job, 0, 1, FAKE)
+    assert ei.value.name == "PS_ERR_DUP_PUSH"
+    with pytest.raises(PsError) as ei:
+        svc.push_flat(job, 1, FAKE)                 # block 0 already has worker 1: nothing marked
+    assert ei.value.name == "PS_ERR_DUP_PUSH"
+    assert svc.job_block_info(job, 1).push_mask == 0
+    svc.push_flat(job, 0, FAKE)
+    svc.push_flat(job, 2, FAKE)
+    assert svc.job_block_info(job, 0).push_mask == 0b111
+    assert svc.job_block_info(job, 1).push_mask == 0b101
+    wave = svc.pack_wave([job])
+    with pytest.raises(PsError) as ei:
+        svc.plan_wave(wave)                          # block 1 lacks worker 1
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    svc.push(job, 1, 1, FAKE)
+    assert svc.plan_wave(wave).n_blocks == 2
+    with pytest.raises(PsError) as ei:
+        svc.aggregate(wave)
+    assert ei.value.name == "PS_ERR_NO_DEVICE"
+    assert svc.job_block_info(job, 0).push_mask == 0b111   # refused call consumed nothing
+
+
+def test_plan_validation_and_counts():
+    specs = wl.packed_wave_jobs(42)
+    svc = ParameterService(None)
+    jobs = [reg(svc, s.layer_numel, s.W)[0] for s in specs]
+    for j, s in zip(jobs, specs):
+        for w in range(s.W):
+            svc.push_flat(j, w, FAKE)
+    wave = svc.pack_wave(jobs)
+    st = svc.plan_wave(wave)
+    sizes = [(svc.job_block_info(j, b).numel, specs[jobs.index(j)].W) for j, b in wave.tolist()]
+    assert st.n_blocks == 1743 and st.n_params == 900_022_044
+    assert st.algorithmic_bytes == sum((4 * W + 16) * n for n, W in sizes)
+    assert st.n_large_tiles == sum(-(-n // 4096) for n, _ in sizes if n > 4096)
+    small = [n for n, _ in sizes if n <= 4096]
+    assert st.n_small_blocks == len(small) and st.small_params == sum(small)
+    quads = sum(-(-n // 4) for n in small)
+    assert -(-quads // 2048) <= st.n_small_bins <= len(small)
+    refs = wave.tolist()
+    for bad, name in [(refs + [refs[3]], "PS_ERR_DUP_BLOCK"), ([(99, 0)], "PS_ERR_BAD_JOB"),
+                      ([(jobs[0], 10_000)], "PS_ERR_BAD_BLOCK"), ([(jobs[0], -1)], "PS_ERR_BAD_BLOCK")]:
+        with pytest.raises(PsError) as ei:
+            svc.plan_wave(WaveList(bad))
+        assert ei.value.name == name
+    assert svc.plan_wave(WaveList([])).n_blocks == 0
+
+
+def test_argument_errors_and_unregister():
+    L = load_library()
+    ctx = C.c_void_p()
+    for cfg in (Config(1000, 0, 0, None, 0), Config(0, 5000, 0, None, 0), Config(0, 0, 8, None, 0),
+                Config(0, 0, 0, 128, 1 << 20)):
+        assert L.ps_create(C.byref(cfg), C.byref(ctx)) == -1
+    svc = ParameterService(None)
+    for layers, W, lr in [([0], 2, 0.1), ([10], 0, 0.1), ([10], 33, 0.1), ([], 2, 0.1),
+                          ([10], 2, float("nan")), ([10], 2, float("inf"))]:
+        with pytest.raises(PsError) as ei:
+            svc.register_job(layers, W, lr, 0.9, 0.0)
+        assert ei.value.name == "PS_ERR_ARG"
+    a, _ = reg(svc, [100])
+    b, _ = reg(svc, [100], W=32)
+    assert svc.job_block_info(b, 0).W == 32
+    svc.unregister_job(a)
+    with pytest.raises(PsError) as ei:
+        svc.job_block_info(a, 0)
+    assert ei.value.name == "PS_ERR_BAD_JOB"
+    with pytest.raises(PsError):
+        svc.unregister_job(a)
+    assert svc.job_n_blocks(b) == 1
+    assert load_library().ps_strerror(-6).decode().startswith("block has not")
