@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the aggregation hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: pack
+the wave, push every worker's gradient of every job, aggregate the wave (sum +
+momentum-SGD update + telemetry, large- and small-block kernels), pull.
+Inputs (gradients, parameters, momentum) are resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Workloads: packed_wave (12 concurrent jobs, W in {2,4,8,16}; default), alexnet,
+resnet50, vgg16, mlp.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def specs_for(name: str):
+    import workloads as wl
+    if name == "packed_wave":
+        return wl.packed_wave_jobs(42), 42
+    return [wl.job_config(name)], 0
+
+
+def cpu_baseline(gpu, wave_refs, budget_params: float = 2.5e9):
+    """Time the oracle (one thread, as it stands) on a bounded sample of the same
+    wave: every k-th block of the list, k chosen so the sample holds about
+    budget_params worker-gradient elements.  Returns the JSON object."""
+    import numpy as np
+    import oracle
+    import torch
+
+    job_index = {j: i for i, j in enumerate(gpu.jobs)}
+    sizes = []
+    for j, b in wave_refs:
+        ji = job_index[j]
+        sizes.append(gpu.blocks[ji][b][2] * gpu.specs[ji].W)
+    total = float(sum(sizes))
+    k = max(1, int(round(total / budget_params)))
+    sample = wave_refs[::k]
+    work = []
+    for j, b in sample:
+        ji = job_index[j]
+        s = gpu.specs[ji]
+        layer, off, n, flat = gpu.blocks[ji][b]
+        gs = [gpu.grads[ji][w][flat:flat + n].cpu().numpy() for w in range(s.W)]
+        p = np.full(n, 0.01, dtype=np.float32)
+        v = np.zeros(n, dtype=np.float32)
+        work.append((gs, p, v, s))
+    oracle.lib()
+    t0 = time.perf_counter()
+    for gs, p, v, s in work:
+        oracle.aggregate_block(gs, p, v, s.lr, s.momentum, s.wd)
+    dt = time.perf_counter() - t0
+    n_params = sum(w[1].size for w in work)
+    n_bytes = sum((4 * w[3].W + 16) * w[1].size for w in work)
+    return {
+        "value": n_params / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+        "GB_per_s": n_bytes / dt / 1e9, "seconds": dt,
+        "sample": f"every {k}-th block of the wave list: {len(work)} of {len(wave_refs)} blocks, "
+                  f"{n_params} params, single-threaded C++ oracle on host memory",
+        "host_cpu": _cpu_model(), "host_cores_total": os.cpu_count(),
+    }
+
+
+def _cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="packed_wave")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
+              "and no multi-GPU path exists (see DESIGN.md, 'More than one GPU').", file=sys.stderr)
+        return 2
+
+    import torch
+    from harness import GpuService
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    specs, seed = specs_for(args.workload)
+    t_setup = time.perf_counter()
+    gpu = GpuService(specs, seed)
+    gpu.fill_grads(0)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+    svc = gpu.svc
+
+    def step():
+        wave = svc.pack_wave(gpu.jobs)                       # a3
+        for ji, s in enumerate(specs):                       # a2
+            for w in range(s.W):
+                svc.push_flat(gpu.jobs[ji], w, gpu.grads[ji][w])
+        svc.aggregate(wave)                                  # a4-a7
+        for j in gpu.jobs:                                   # a8
+            svc.pull_flat(j)
+        return wave
+
+    for _ in range(args.warmup):
+        wave = step()
+    torch.cuda.synchronize()
+    for ji, s in enumerate(specs):
+        for w in range(s.W):
+            svc.push_flat(gpu.jobs[ji], w, gpu.grads[ji][w])
+    stats = svc.plan_wave(svc.pack_wave(gpu.jobs))
+    svc.aggregate(svc.pack_wave(gpu.jobs))                   # consume the pushes again
+    torch.cuda.synchronize()
+
+    svc.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wave = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tm = svc.timing_read()
+    svc.timing_enable(False)
+
+    n_params = stats.n_params
+    ms_per_step = dt / args.steps * 1e3
+    value = n_params * args.steps / dt
+    large_bytes = stats.algorithmic_bytes - stats.small_algorithmic_bytes
+    large_ms = tm.large_ms / max(tm.n_waves, 1)
+    achieved = large_bytes / (large_ms * 1e-3) / 1e9 if large_ms > 0 else 0.0
+    out = {
+        "metric": "aggregated params/sec and achieved HBM GB/s (% of MI355X peak), 1 GPU",
+        "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": args.workload, "jobs": len(specs), "W": [s.W for s in specs],
+            "models": [s.model for s in specs], "blocks": stats.n_blocks, "params": n_params,
+            "block_cap_bytes": 4 << 20, "seed": seed,
+            "algorithmic_bytes_per_step": stats.algorithmic_bytes,
+        },
+        "step_GB_per_s": stats.algorithmic_bytes * args.steps / dt / 1e9,
+        "step_frac_of_hbm_peak": stats.algorithmic_bytes * args.steps / dt / 1e9 / HBM_PEAK_GBS,
+        "roofline": {
+            "bound": "hbm", "kernel": "ps_agg_large", "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "algorithmic_bytes_per_launch": large_bytes, "avg_launch_ms": large_ms,
+            "launches": tm.n_waves,
+        },
+        "kernels_ms_per_wave": {
+            "upload": tm.upload_ms / max(tm.n_waves, 1), "ps_agg_large": large_ms,
+            "ps_agg_small": tm.small_ms / max(tm.n_waves, 1),
+            "ps_block_norms": tm.norms_ms / max(tm.n_waves, 1),
+            "gpu_total": tm.total_ms / max(tm.n_waves, 1),
+        },
+        "small_path": {"blocks": stats.n_small_blocks, "bins": stats.n_small_bins,
+                       "params": stats.small_params},
+        "setup_seconds": t_setup,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(gpu, wave.tolist())
+    gpu.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -119,7 +119,17 @@ typedef struct ps_wave_stats {
   int64_t n_small_bins;    /* workgroups of the small-block kernel */
   int64_t small_params;    /* parameters in small-path blocks */
   uint64_t algorithmic_bytes; /* sum over blocks of (4 W + 16) * numel */
+  uint64_t small_algorithmic_bytes; /* the part of that in small-path blocks */
 } ps_wave_stats;
+
+typedef struct ps_timing {
+  int64_t n_waves;     /* waves measured since ps_timing_enable */
+  double upload_ms;    /* host->device copy of the wave's tables */
+  double large_ms;     /* large-block kernel */
+  double small_ms;     /* small-block kernel */
+  double norms_ms;     /* per-block telemetry reduction */
+  double total_ms;     /* first to last of the above, GPU time (sums over waves) */
+} ps_timing;
 
 /* --- life cycle ---------------------------------------------------------- */
 
@@ -220,6 +230,15 @@ int32_t ps_pull_flat(ps_ctx* ctx, ps_job_t job, const float** out_param_dev,
  * into host-visible memory at the end of the wave: the caller must have
  * synchronised the wave's stream before reading. */
 int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* out);
+
+/* --- measurement ------------------------------------------------------------ */
+
+/* on != 0: from now on every ps_aggregate brackets its copy and each of its
+ * kernels with HIP events on the wave's stream, and the elapsed times are
+ * summed per kind.  Resets the sums.  on == 0 stops it. */
+int32_t ps_timing_enable(ps_ctx* ctx, int32_t on);
+/* Wait for every wave this context has enqueued, then report the sums. */
+int32_t ps_timing_read(ps_ctx* ctx, ps_timing* out);
 
 /* --- diagnostics ----------------------------------------------------------- */
 

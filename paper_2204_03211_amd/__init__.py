@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     BlockStats,
     ParameterService,
     PsError,
+    Timing,
     WaveList,
     WaveStats,
     load_library,

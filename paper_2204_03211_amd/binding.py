@@ -53,14 +53,20 @@ class BlockStats(C.Structure):
 class WaveStats(C.Structure):
     _fields_ = [("n_blocks", C.c_int64), ("n_params", C.c_int64), ("n_large_tiles", C.c_int64),
                 ("n_small_blocks", C.c_int64), ("n_small_bins", C.c_int64),
-                ("small_params", C.c_int64), ("algorithmic_bytes", C.c_uint64)]
+                ("small_params", C.c_int64), ("algorithmic_bytes", C.c_uint64),
+                ("small_algorithmic_bytes", C.c_uint64)]
+
+
+class Timing(C.Structure):
+    _fields_ = [("n_waves", C.c_int64), ("upload_ms", C.c_double), ("large_ms", C.c_double),
+                ("small_ms", C.c_double), ("norms_ms", C.c_double), ("total_ms", C.c_double)]
 
 
 EXPORTS = [
     "ps_create", "ps_destroy", "ps_job_arena_bytes", "ps_register_job", "ps_unregister_job",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
     "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat",
-    "ps_telemetry", "ps_strerror", "ps_last_error", "ps_version",
+    "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
 ]
 
 _lib = None
@@ -97,6 +103,8 @@ def load_library() -> C.CDLL:
     L.ps_pull_momentum.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_flat.argtypes = [vp, i32, P(vp), P(vp), P(i64)]
     L.ps_telemetry.argtypes = [vp, i32, i32, P(BlockStats)]
+    L.ps_timing_enable.argtypes = [vp, i32]
+    L.ps_timing_read.argtypes = [vp, P(Timing)]
     L.ps_strerror.argtypes = [i32]
     L.ps_strerror.restype = C.c_char_p
     L.ps_last_error.argtypes = [vp]
@@ -264,6 +272,14 @@ class ParameterService:
     def telemetry(self, job: int, block: int) -> BlockStats:
         out = BlockStats()
         self._check(self.L.ps_telemetry(self.ctx, job, block, C.byref(out)))
+        return out
+
+    def timing_enable(self, on: bool) -> None:
+        self._check(self.L.ps_timing_enable(self.ctx, 1 if on else 0))
+
+    def timing_read(self) -> Timing:
+        out = Timing()
+        self._check(self.L.ps_timing_read(self.ctx, C.byref(out)))
         return out
 
     def version(self) -> int:

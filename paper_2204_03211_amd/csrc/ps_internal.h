@@ -58,6 +58,9 @@ struct PsWaveTables {
   const uint32_t* large_blocks;  // descriptor indices of large-path blocks
   uint32_t n_large_blocks;
   bool fp_contract;
+  // optional hipEvent_t handles recorded before the large kernel and after each
+  // of the three kernels (all NULL = no timing)
+  void* ev[4];
 };
 
 // Enqueue the kernels of one wave on stream (a hipStream_t).  Returns a

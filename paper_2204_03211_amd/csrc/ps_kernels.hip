@@ -287,6 +287,10 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const PsBlockDesc* __res
 
 int ps_launch_wave(const PsWaveTables& t, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  auto mark = [&](int i) {
+    if (t.ev[i]) (void)hipEventRecord(static_cast<hipEvent_t>(t.ev[i]), stream);
+  };
+  mark(0);
   if (t.n_tiles) {
     if (t.fp_contract)
       hipLaunchKernelGGL(ps_agg_large<true>, dim3(t.n_tiles), dim3(PS_WG), 0, stream, t.desc, t.gptr,
@@ -295,6 +299,7 @@ int ps_launch_wave(const PsWaveTables& t, void* stream_) {
       hipLaunchKernelGGL(ps_agg_large<false>, dim3(t.n_tiles), dim3(PS_WG), 0, stream, t.desc, t.gptr,
                          t.tiles, t.tile_part);
   }
+  mark(1);
   if (t.n_bins) {
     if (t.fp_contract)
       hipLaunchKernelGGL(ps_agg_small<true>, dim3(t.n_bins), dim3(PS_WG), 0, stream, t.desc, t.gptr,
@@ -303,10 +308,12 @@ int ps_launch_wave(const PsWaveTables& t, void* stream_) {
       hipLaunchKernelGGL(ps_agg_small<false>, dim3(t.n_bins), dim3(PS_WG), 0, stream, t.desc, t.gptr,
                          t.small_entries, t.bins);
   }
+  mark(2);
   if (t.n_large_blocks) {
     const uint32_t per = PS_WG / 64;
     hipLaunchKernelGGL(ps_block_norms, dim3((t.n_large_blocks + per - 1) / per), dim3(PS_WG), 0,
                        stream, t.desc, t.large_blocks, t.n_large_blocks, t.tile_part);
   }
+  mark(3);
   return (int)hipGetLastError();
 }

@@ -61,6 +61,8 @@ struct Slot {
   size_t host_cap = 0, dev_cap = 0;
   hipEvent_t done = nullptr;
   bool in_flight = false;
+  hipEvent_t tev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};  // timing marks
+  bool timed = false;
 };
 constexpr int kSlots = 4;
 
@@ -87,6 +89,8 @@ struct ps_ctx {
   int next_slot = 0;
   Plan plan;
   std::string last_error;
+  bool timing_on = false;
+  ps_timing timing{};
 };
 
 namespace {
@@ -202,6 +206,7 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     P.desc.push_back(d);
     P.stats.n_params += d.n;
     P.stats.algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
+    if (d.n <= small_max) P.stats.small_algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
   }
   close_bin();
   P.stats.n_blocks = n;
@@ -210,10 +215,31 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
   return PS_OK;
 }
 
+// Wait for the wave that last used the slot and add its event times to the sums.
+int32_t slot_retire(ps_ctx* c, Slot& s) {
+  if (!s.in_flight) return PS_OK;
+  PS_HIP(c, hipEventSynchronize(s.done));
+  s.in_flight = false;
+  if (s.timed) {
+    s.timed = false;
+    float ms[4] = {0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], s.tev[i], s.tev[i + 1]));
+    float tot = 0;
+    PS_HIP(c, hipEventElapsedTime(&tot, s.tev[0], s.tev[4]));
+    c->timing.n_waves += 1;
+    c->timing.upload_ms += ms[0];
+    c->timing.large_ms += ms[1];
+    c->timing.small_ms += ms[2];
+    c->timing.norms_ms += ms[3];
+    c->timing.total_ms += tot;
+  }
+  return PS_OK;
+}
+
 int32_t slot_reserve(ps_ctx* c, Slot& s, size_t host_bytes, size_t dev_bytes) {
-  if (s.in_flight) {
-    PS_HIP(c, hipEventSynchronize(s.done));
-    s.in_flight = false;
+  {
+    const int32_t st = slot_retire(c, s);
+    if (st != PS_OK) return st;
   }
   if (!s.done) PS_HIP(c, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
   if (host_bytes > s.host_cap) {
@@ -286,6 +312,8 @@ void ps_destroy(ps_ctx* c) {
   for (Slot& s : c->slots) {
     if (s.in_flight) (void)hipEventSynchronize(s.done);
     if (s.done) (void)hipEventDestroy(s.done);
+    for (hipEvent_t e : s.tev)
+      if (e) (void)hipEventDestroy(e);
     if (s.host) (void)hipHostFree(s.host);
     if (s.dev) (void)hipFree(s.dev);
   }
@@ -538,8 +566,14 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   put(o_large, P.large_blocks.data(), P.large_blocks.size() * sizeof(uint32_t));
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
   PsWaveTables t{};
+  if (c->timing_on) {
+    for (int i = 0; i < 5; ++i)
+      if (!s.tev[i]) PS_HIP(c, hipEventCreate(&s.tev[i]));
+    PS_HIP(c, hipEventRecord(s.tev[0], hs));
+    for (int i = 0; i < 4; ++i) t.ev[i] = s.tev[i + 1];
+  }
+  PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
   t.desc = reinterpret_cast<const PsBlockDesc*>(s.dev + o_desc);
   t.gptr = reinterpret_cast<const float* const*>(s.dev + o_gptr);
   t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
@@ -555,6 +589,7 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   if (le != 0) return hip_fail(c, (hipError_t)le, "launching the wave");
   PS_HIP(c, hipEventRecord(s.done, hs));
   s.in_flight = true;
+  s.timed = c->timing_on;
 
   // the wave is enqueued: consume the pushes
   for (int64_t i = 0; i < n; ++i) {
@@ -602,6 +637,30 @@ int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const
   if (out_param_dev) *out_param_dev = j->p;
   if (out_mom_dev) *out_mom_dev = j->v;
   if (out_flat_numel) *out_flat_numel = j->flat_numel;
+  return PS_OK;
+}
+
+int32_t ps_timing_enable(ps_ctx* c, int32_t on) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
+  for (Slot& s : c->slots) {
+    const int32_t st = slot_retire(c, s);
+    if (st != PS_OK) return st;
+  }
+  c->timing = ps_timing{};
+  c->timing_on = on != 0;
+  return PS_OK;
+}
+
+int32_t ps_timing_read(ps_ctx* c, ps_timing* out) {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  for (Slot& s : c->slots) {
+    const int32_t st = slot_retire(c, s);
+    if (st != PS_OK) return st;
+  }
+  *out = c->timing;
   return PS_OK;
 }
 
