@@ -10,7 +10,9 @@ region.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
 Workloads: packed_wave (12 concurrent jobs, W in {2,4,8,16}; default), alexnet,
-resnet50, vgg16, mlp.
+resnet50, vgg16, mlp.  --copy-calibration instead runs a plain 1 GiB device copy
+a few times, so that profiler byte counters can be scaled by a kernel of known
+traffic.
 """
 from __future__ import annotations
 
@@ -35,7 +37,7 @@ def specs_for(name: str):
     return [wl.job_config(name)], 0
 
 
-def cpu_baseline(gpu, wave_refs, budget_params: float = 2.5e9):
+def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
     """Time the oracle (one thread, as it stands) on a bounded sample of the same
     wave: every k-th block of the list, k chosen so the sample holds about
     budget_params worker-gradient elements.  Returns the JSON object."""
@@ -93,6 +95,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="packed_wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
@@ -103,6 +106,17 @@ def main() -> int:
     from harness import GpuService
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)              # an elementwise kernel: 1 read, 1 write
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read": 4 * n, "bytes_written": 4 * n,
+                          "launches": 5}))
+        return 0
     specs, seed = specs_for(args.workload)
     t_setup = time.perf_counter()
     gpu = GpuService(specs, seed)
