@@ -75,7 +75,7 @@ typedef struct ps_ctx ps_ctx;
 typedef int32_t ps_job_t;
 
 typedef struct ps_config {
-  uint64_t max_block_bytes;   /* 0 = PS_DEFAULT_BLOCK_BYTES; must be a multiple of 256 */
+  uint64_t max_block_bytes;   /* 0 = PS_DEFAULT_BLOCK_BYTES; a multiple of 256, at most 1 GiB */
   uint32_t small_block_elems; /* blocks of at most this many values take the small-block
                                  path; 0 = PS_DEFAULT_SMALL_ELEMS; at most 4096 */
   uint32_t flags;             /* PS_FLAG_* */
@@ -103,7 +103,7 @@ typedef struct ps_block_info {
                              ps_push_flat, a worker's gradient buffer share this layout. */
   int64_t round;          /* aggregations applied to this block so far */
   uint32_t push_mask;     /* bit w set = worker w has pushed for the current round */
-  uint32_t small_path;    /* 1 if the block takes the small-block kernel */
+  uint32_t small_path;    /* 1 if the block takes the small-block path */
 } ps_block_info;
 
 typedef struct ps_block_stats {
@@ -114,21 +114,22 @@ typedef struct ps_block_stats {
 typedef struct ps_wave_stats {
   int64_t n_blocks;        /* blocks in the list */
   int64_t n_params;        /* sum of their numel */
-  int64_t n_large_tiles;   /* workgroups of the large-block kernel */
-  int64_t n_small_blocks;  /* blocks routed to the small-block kernel */
-  int64_t n_small_bins;    /* workgroups of the small-block kernel */
+  int64_t n_large_tiles;   /* workgroups taking a tile of a large-path block */
+  int64_t n_small_blocks;  /* blocks routed to the small-block path */
+  int64_t n_small_bins;    /* workgroups taking a bin of small-path blocks */
   int64_t small_params;    /* parameters in small-path blocks */
   uint64_t algorithmic_bytes; /* sum over blocks of (4 W + 16) * numel */
   uint64_t small_algorithmic_bytes; /* the part of that in small-path blocks */
+  int64_t n_launches;      /* aggregation kernel launches the list is cut into */
 } ps_wave_stats;
 
 typedef struct ps_timing {
   int64_t n_waves;     /* waves measured since ps_timing_enable */
+  int64_t n_launches;  /* aggregation kernel launches in those waves */
   double upload_ms;    /* host->device copy of the wave's tables */
-  double large_ms;     /* large-block kernel */
-  double small_ms;     /* small-block kernel */
+  double agg_ms;       /* the aggregation launches, first start to last end */
   double norms_ms;     /* per-block telemetry reduction */
-  double total_ms;     /* first to last of the above, GPU time (sums over waves) */
+  double total_ms;     /* all of the above, GPU time (sums over waves) */
 } ps_timing;
 
 /* --- life cycle ---------------------------------------------------------- */

@@ -54,12 +54,12 @@ class WaveStats(C.Structure):
     _fields_ = [("n_blocks", C.c_int64), ("n_params", C.c_int64), ("n_large_tiles", C.c_int64),
                 ("n_small_blocks", C.c_int64), ("n_small_bins", C.c_int64),
                 ("small_params", C.c_int64), ("algorithmic_bytes", C.c_uint64),
-                ("small_algorithmic_bytes", C.c_uint64)]
+                ("small_algorithmic_bytes", C.c_uint64), ("n_launches", C.c_int64)]
 
 
 class Timing(C.Structure):
-    _fields_ = [("n_waves", C.c_int64), ("upload_ms", C.c_double), ("large_ms", C.c_double),
-                ("small_ms", C.c_double), ("norms_ms", C.c_double), ("total_ms", C.c_double)]
+    _fields_ = [("n_waves", C.c_int64), ("n_launches", C.c_int64), ("upload_ms", C.c_double),
+                ("agg_ms", C.c_double), ("norms_ms", C.c_double), ("total_ms", C.c_double)]
 
 
 EXPORTS = [

@@ -5,62 +5,82 @@
 
 #include <stdint.h>
 
-// One block of one job as the kernels see it.  64 bytes so that a descriptor
-// never straddles a cache line and can be fetched with four s_load_dwordx4.
-struct PsBlockDesc {
+// One block of one job as the kernels see it: a 64-byte header followed
+// directly by the block's W gradient pointers (worker order).  Header and
+// pointers are fetched together once a tile names the record.
+struct PsBlockRec {
   float* p;          // parameter shard (device, 256-byte aligned)
   float* v;          // momentum shard
   double* stat;      // where sum S^2 of this block goes (host-visible memory)
-  uint32_t gofs;     // index of worker 0's pointer in the wave's gradient-pointer table
   uint32_t n;        // elements in the block
   uint32_t W;        // workers
   uint32_t tile0;    // large path: first of this block's entries in the tile-partials array
   uint32_t ntiles;   // large path: number of tiles
   float lr, mu, wd;
-  uint32_t pad_[2];
+  uint32_t pad_[3];
+  // const float* grad[W] follows
 };
-static_assert(sizeof(PsBlockDesc) == 64, "descriptor must stay 64 bytes");
+static_assert(sizeof(PsBlockRec) == 64, "record header must stay 64 bytes");
 
-// Large path: one workgroup per tile = (descriptor, first element).
+// Records live in one byte array; they are named by their offset in 8-byte units.
+constexpr uint32_t PS_REC_UNIT = 8;
+
+// Large path: one workgroup per tile = (record, first element of the tile).
 struct PsTile {
-  uint32_t desc;
+  uint32_t rec;
   uint32_t off;
 };
 
 // Small path: one workgroup per bin of consecutive entries.  An entry names a
-// descriptor and the position of the block's first 16-byte quad in the bin.
+// record and the position of the block's first 16-byte quad in the bin.
 struct PsSmallEntry {
-  uint32_t desc;
-  uint32_t qstart;
+  uint32_t rec;
+  uint32_t qstart;  // first quad of the block in the bin
+  uint32_t pstart;  // first gradient pointer of the block in the bin's pointer list
+  uint32_t pad_;
 };
 struct PsBin {
   uint32_t first;   // first entry
   uint32_t count;   // entries in the bin (<= PS_BIN_MAX_BLOCKS)
   uint32_t quads;   // total quads (<= PS_BIN_MAX_QUADS)
-  uint32_t pad_;
+  uint32_t nptrs;   // gradient pointers of all entries together (<= PS_BIN_MAX_PTRS)
+};
+
+// A contiguous run of tiles launched as one kernel.
+struct PsChunk {
+  uint32_t begin, end;
 };
 
 constexpr uint32_t PS_WG = 256;                 // threads per workgroup (4 wavefronts)
-constexpr uint32_t PS_TILE_QUADS_PER_LANE = 4;  // 16-byte loads per lane per stream in a full tile
+constexpr uint32_t PS_TILE_QUADS_PER_LANE = 4;  // 16-byte accesses per lane per stream in a tile
 constexpr uint32_t PS_TILE_ELEMS = PS_WG * 4 * PS_TILE_QUADS_PER_LANE;  // 4096
 constexpr uint32_t PS_BIN_MAX_BLOCKS = 64;
-constexpr uint32_t PS_BIN_MAX_QUADS = 2048;
+constexpr uint32_t PS_BIN_MAX_QUADS = 1024;  // >= quads of the largest small-path block
+constexpr uint32_t PS_BIN_MAX_PTRS = 1024;
+constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path accepts
+
+// Tiles per launch of the large path, by worker count.  All workgroups of one
+// launch are resident together, start together and therefore reach their
+// stores at about the same time, which keeps HBM reads and writes from
+// interleaving finely; the more read streams a tile has, the more that matters.
+inline uint32_t ps_chunk_tiles(uint32_t W) { return W >= 12 ? 1024u : (W >= 6 ? 1536u : 2048u); }
 
 struct PsWaveTables {
-  const PsBlockDesc* desc;
-  const float* const* gptr;
-  const PsTile* tiles;
+  const unsigned char* recs;     // PsBlockRec records
+  const PsTile* tiles;           // sorted so that tiles of one worker count are adjacent
   uint32_t n_tiles;
+  const PsChunk* chunks;         // HOST array: launch ranges over tiles
+  uint32_t n_chunks;
   double* tile_part;             // n_tiles doubles, device scratch
   const PsSmallEntry* small_entries;
   const PsBin* bins;
   uint32_t n_bins;
-  const uint32_t* large_blocks;  // descriptor indices of large-path blocks
+  const uint32_t* large_recs;    // record offsets of large-path blocks
   uint32_t n_large_blocks;
   bool fp_contract;
-  // optional hipEvent_t handles recorded before the large kernel and after each
-  // of the three kernels (all NULL = no timing)
-  void* ev[4];
+  // optional hipEvent_t handles recorded before the first launch, after the
+  // aggregation launches, and after the telemetry reduction (NULL = no timing)
+  void* ev[3];
 };
 
 // Enqueue the kernels of one wave on stream (a hipStream_t).  Returns a

@@ -6,8 +6,8 @@
 //     d = S + wd*p ; v' = mu*v + d ; p' = p - lr*v'
 // every operation rounded on its own.  The work is a streaming reduction:
 // (4W + 16) bytes of HBM traffic per parameter against W + 7 flops, so the
-// kernels are built around 16-byte coalesced loads with many of them in flight
-// per lane; there is no contraction here for the matrix cores to do.
+// kernels are built around 16-byte coalesced accesses with many of them in
+// flight per lane; there is no contraction here for the matrix cores to do.
 //
 // Build with -ffp-contract=off; the pragma below says the same to the compiler
 // for this translation unit regardless of the command line.
@@ -20,15 +20,24 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-constexpr int PS_MAX_W_UNROLLED = 16;  // largest worker count with a fully unrolled tile body
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ f32x4 load_stream(const float* a) {
-  // gradients, parameters and momentum are touched once per wave: keep them
-  // from displacing anything useful in L2
-  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a));
+// Cache policy of every streaming access: non-temporal.  Gradients, parameters
+// and momentum are touched once per wave; measured on MI355X the hint is worth
+// about 10 % of bandwidth on loads and on stores alike.
+constexpr int kStream = 2;  // the "nt" bit of the buffer instructions' cache-policy field
+
+// A raw buffer descriptor over `bytes` bytes at p.  Dword-x4 buffer accesses are
+// range-checked per component: components past the end load as zero and are not
+// stored, which is how a block's ragged tail is handled without a scalar path.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t span(const float* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p), 0, bytes, 0x00020000);
 }
-__device__ __forceinline__ void store_stream(float* a, f32x4 x) {
-  __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(a));
+__device__ __forceinline__ f32x4 load4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kStream));
+}
+__device__ __forceinline__ void store4(__amdgpu_buffer_rsrc_t r, uint32_t byte_off, f32x4 x) {
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, x), r, byte_off, 0, kStream);
 }
 
 template <bool FMA>
@@ -70,179 +79,132 @@ __device__ __forceinline__ double wave_sum(double a) {
   return a;
 }
 
-// A full tile: PS_TILE_ELEMS elements, no bounds checks.  W > 0 is a
-// compile-time worker count (loads of all streams can be issued up front);
-// W == 0 takes the count at run time.
+// ---------------------------------------------------------------------------
+// Large path: one tile (up to PS_TILE_ELEMS elements of one block) per
+// workgroup.  W > 0: worker count known at compile time, so the loads of all
+// W + 2 streams are issued before the first add.  W == 0: run-time count.
+// ---------------------------------------------------------------------------
 template <int W, bool FMA>
-__device__ __forceinline__ double tile_full(const float* const* __restrict__ gp, uint32_t w_rt,
-                                            float* __restrict__ p, float* __restrict__ v, float lr,
-                                            float mu, float wd, uint32_t tid) {
+__device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
+                                            const float* const* __restrict__ gp, uint32_t w_rt,
+                                            uint32_t off, uint32_t bytes, uint32_t tid) {
   constexpr int U = PS_TILE_QUADS_PER_LANE;
+  const float lr = r->lr, mu = r->mu, wd = r->wd;
   f32x4 acc[U];
-  const uint32_t nw = W > 0 ? (uint32_t)W : w_rt;
   {
-    const float* g0 = gp[0];
+    const __amdgpu_buffer_rsrc_t g0 = span(gp[0] + off, bytes);
 #pragma unroll
-    for (int u = 0; u < U; ++u) acc[u] = load_stream(g0 + (u * PS_WG + tid) * 4);
+    for (int u = 0; u < U; ++u) acc[u] = load4(g0, (u * PS_WG + tid) * 16);
   }
   if constexpr (W > 0) {
 #pragma unroll
     for (int w = 1; w < W; ++w) {
-      const float* gw = gp[w];
+      const __amdgpu_buffer_rsrc_t gw = span(gp[w] + off, bytes);
 #pragma unroll
-      for (int u = 0; u < U; ++u) acc[u] = acc[u] + load_stream(gw + (u * PS_WG + tid) * 4);
+      for (int u = 0; u < U; ++u) acc[u] = acc[u] + load4(gw, (u * PS_WG + tid) * 16);
     }
   } else {
-    for (uint32_t w = 1; w < nw; ++w) {
-      const float* gw = gp[w];
+    for (uint32_t w = 1; w < w_rt; ++w) {
+      const __amdgpu_buffer_rsrc_t gw = span(gp[w] + off, bytes);
 #pragma unroll
-      for (int u = 0; u < U; ++u) acc[u] = acc[u] + load_stream(gw + (u * PS_WG + tid) * 4);
+      for (int u = 0; u < U; ++u) acc[u] = acc[u] + load4(gw, (u * PS_WG + tid) * 16);
     }
   }
-  double a = 0.0;
+  const __amdgpu_buffer_rsrc_t rp = span(r->p + off, bytes), rv = span(r->v + off, bytes);
+  f32x4 pp[U], vv[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
-    const uint32_t e = (u * PS_WG + tid) * 4;
-    f32x4 pp = load_stream(p + e);
-    f32x4 vv = load_stream(v + e);
-    a = update4<FMA>(acc[u], pp, vv, lr, mu, wd, a);
-    store_stream(p + e, pp);
-    store_stream(v + e, vv);
+    pp[u] = load4(rp, (u * PS_WG + tid) * 16);
+    vv[u] = load4(rv, (u * PS_WG + tid) * 16);
   }
-  return a;
-}
-
-// Any run of len elements starting at a 16-byte aligned address: whole quads
-// with 16-byte accesses, the last 1..3 elements one by one.
-template <bool FMA>
-__device__ __forceinline__ double quad_any(const float* const* __restrict__ gp, uint32_t nw,
-                                           float* __restrict__ p, float* __restrict__ v, float lr,
-                                           float mu, float wd, uint32_t e, uint32_t rem) {
   double a = 0.0;
-  if (rem >= 4) {
-    f32x4 s = load_stream(gp[0] + e);
-    for (uint32_t w = 1; w < nw; ++w) s = s + load_stream(gp[w] + e);
-    f32x4 pp = load_stream(p + e);
-    f32x4 vv = load_stream(v + e);
-    a = update4<FMA>(s, pp, vv, lr, mu, wd, a);
-    store_stream(p + e, pp);
-    store_stream(v + e, vv);
-  } else {
-    for (uint32_t k = 0; k < rem; ++k) {
-      float s = gp[0][e + k];
-      for (uint32_t w = 1; w < nw; ++w) s = s + gp[w][e + k];
-      float pk = p[e + k], vk = v[e + k];
-      update1<FMA>(s, pk, vk, lr, mu, wd);
-      p[e + k] = pk;
-      v[e + k] = vk;
-      const double sd = (double)s;
-      a = __builtin_fma(sd, sd, a);
-    }
+#pragma unroll
+  for (int u = 0; u < U; ++u) a = update4<FMA>(acc[u], pp[u], vv[u], lr, mu, wd, a);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    store4(rp, (u * PS_WG + tid) * 16, pp[u]);
+    store4(rv, (u * PS_WG + tid) * 16, vv[u]);
   }
   return a;
 }
 
-// ---------------------------------------------------------------------------
-// Large path: one workgroup per tile of a block.
-// ---------------------------------------------------------------------------
 template <bool FMA>
-__global__ __launch_bounds__(PS_WG) void ps_agg_large(const PsBlockDesc* __restrict__ desc,
-                                                      const float* const* __restrict__ gptr,
-                                                      const PsTile* __restrict__ tiles,
-                                                      double* __restrict__ tile_part) {
-  const uint32_t t = blockIdx.x;
+__device__ __forceinline__ void large_tile(const unsigned char* __restrict__ recs, PsTile te,
+                                           uint32_t slot, double* __restrict__ tile_part) {
   const uint32_t tid = threadIdx.x;
-  const PsTile te = tiles[t];
-  const uint32_t di = __builtin_amdgcn_readfirstlane(te.desc);
+  const uint32_t ro = __builtin_amdgcn_readfirstlane(te.rec);
   const uint32_t off = __builtin_amdgcn_readfirstlane(te.off);
-  const PsBlockDesc* __restrict__ d = desc + di;
-  const uint32_t n = d->n, W = d->W;
-  const float lr = d->lr, mu = d->mu, wd = d->wd;
-  float* __restrict__ p = d->p + off;
-  float* __restrict__ v = d->v + off;
-  const float* const* __restrict__ gp0 = gptr + d->gofs;
-  const uint32_t len = min(PS_TILE_ELEMS, n - off);
+  const PsBlockRec* __restrict__ r =
+      reinterpret_cast<const PsBlockRec*>(recs + (size_t)ro * PS_REC_UNIT);
+  const float* const* __restrict__ gp = reinterpret_cast<const float* const*>(r + 1);
+  const uint32_t W = r->W;
+  const uint32_t left = r->n - off;
+  const uint32_t bytes = (left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
 
-  double a = 0.0;
-  if (len == PS_TILE_ELEMS) {
-    // the tile's W gradient pointers, advanced to the tile (uniform: SGPRs)
-    const float* gp[PS_MAX_W_UNROLLED];
-    switch (W) {
-#define PS_CASE(WW)                                                            \
-  case WW: {                                                                   \
-    _Pragma("unroll") for (int w = 0; w < WW; ++w) gp[w] = gp0[w] + off;       \
-    a = tile_full<WW, FMA>(gp, WW, p, v, lr, mu, wd, tid);                     \
-  } break;
-      PS_CASE(1)
-      PS_CASE(2)
-      PS_CASE(4)
-      PS_CASE(8)
-      PS_CASE(16)
-#undef PS_CASE
-      default: {
-        // any other worker count: run-time loop over a pointer table advanced on the fly
-        constexpr int U = PS_TILE_QUADS_PER_LANE;
-        f32x4 acc[U];
-        const float* g0 = gp0[0] + off;
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[u] = load_stream(g0 + (u * PS_WG + tid) * 4);
-        for (uint32_t w = 1; w < W; ++w) {
-          const float* gw = gp0[w] + off;
-#pragma unroll
-          for (int u = 0; u < U; ++u) acc[u] = acc[u] + load_stream(gw + (u * PS_WG + tid) * 4);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const uint32_t e = (u * PS_WG + tid) * 4;
-          f32x4 pp = load_stream(p + e);
-          f32x4 vv = load_stream(v + e);
-          a = update4<FMA>(acc[u], pp, vv, lr, mu, wd, a);
-          store_stream(p + e, pp);
-          store_stream(v + e, vv);
-        }
-      }
-    }
-  } else {
-    // ragged last tile of a block
-    for (uint32_t q = tid; q * 4 < len; q += PS_WG) {
-      const uint32_t e = q * 4;
-      // quad_any indexes the gradient streams from the block start
-      a += quad_any<FMA>(gp0, W, d->p, d->v, lr, mu, wd, off + e, len - e);
-    }
+  double a;
+  switch (W) {
+    case 1: a = tile_body<1, FMA>(r, gp, 1, off, bytes, tid); break;
+    case 2: a = tile_body<2, FMA>(r, gp, 2, off, bytes, tid); break;
+    case 4: a = tile_body<4, FMA>(r, gp, 4, off, bytes, tid); break;
+    case 8: a = tile_body<8, FMA>(r, gp, 8, off, bytes, tid); break;
+    case 16: a = tile_body<16, FMA>(r, gp, 16, off, bytes, tid); break;
+    default: a = tile_body<0, FMA>(r, gp, W, off, bytes, tid); break;
   }
 
   a = wave_sum(a);
   __shared__ double red[PS_WG / 64];
   if ((tid & 63) == 0) red[tid >> 6] = a;
   __syncthreads();
-  if (tid == 0) tile_part[t] = ((red[0] + red[1]) + red[2]) + red[3];
+  if (tid == 0) tile_part[slot] = ((red[0] + red[1]) + red[2]) + red[3];
 }
 
 // ---------------------------------------------------------------------------
-// Small path: one workgroup per bin of tiny blocks.  Descriptors and the bin's
-// quad prefix are staged in LDS; lanes are spread over the concatenated quads of
-// all blocks in the bin, so a 64-element bias next to a 1000-element one still
-// fills whole wavefronts with 16-byte accesses.  Per-quad telemetry partials go
-// through LDS and are reduced per block in a fixed order.
+// Small path: one workgroup per bin of tiny blocks.  Record headers, the bin's
+// quad prefix and all gradient pointers of the bin are staged in LDS; lanes are
+// spread over the concatenated 16-byte quads of all blocks in the bin, so a
+// 64-element bias next to a 1000-element one still fills whole wavefronts with
+// 16-byte accesses.  Per-quad telemetry partials go through LDS and are reduced
+// per block in a fixed order.
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ f32x4 gload4(const float* a) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a));
+}
+
 template <bool FMA>
-__global__ __launch_bounds__(PS_WG) void ps_agg_small(const PsBlockDesc* __restrict__ desc,
-                                                      const float* const* __restrict__ gptr,
-                                                      const PsSmallEntry* __restrict__ entries,
-                                                      const PsBin* __restrict__ bins) {
-  __shared__ PsBlockDesc sd[PS_BIN_MAX_BLOCKS];
-  __shared__ uint32_t qs[PS_BIN_MAX_BLOCKS + 1];
+__device__ __forceinline__ void small_bin(const unsigned char* __restrict__ recs,
+                                          const PsSmallEntry* __restrict__ entries, PsBin bin) {
+  __shared__ PsBlockRec sd[PS_BIN_MAX_BLOCKS];
+  __shared__ uint32_t srec[PS_BIN_MAX_BLOCKS];
+  __shared__ uint32_t qs[PS_BIN_MAX_BLOCKS + 1];   // first quad of each entry
+  __shared__ uint32_t ps[PS_BIN_MAX_BLOCKS + 1];   // first pointer of each entry
+  __shared__ const float* sptr[PS_BIN_MAX_PTRS];
   __shared__ double qpart[PS_BIN_MAX_QUADS];
 
   const uint32_t tid = threadIdx.x;
-  const PsBin bin = bins[blockIdx.x];
-  const uint32_t count = bin.count, quads = bin.quads;
+  const uint32_t count = bin.count, quads = bin.quads, nptrs = bin.nptrs;
   if (tid < count) {
     const PsSmallEntry e = entries[bin.first + tid];
-    sd[tid] = desc[e.desc];
+    const PsBlockRec* r = reinterpret_cast<const PsBlockRec*>(recs + (size_t)e.rec * PS_REC_UNIT);
+    sd[tid] = *r;
+    srec[tid] = e.rec;
     qs[tid] = e.qstart;
+    ps[tid] = e.pstart;
   }
-  if (tid == 0) qs[count] = quads;
+  if (tid == 0) {
+    qs[count] = quads;
+    ps[count] = nptrs;
+  }
+  __syncthreads();
+  for (uint32_t i = tid; i < nptrs; i += PS_WG) {
+    uint32_t lo = 0, hi = count;  // largest lo with ps[lo] <= i
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (ps[mid] <= i) lo = mid; else hi = mid;
+    }
+    const float* const* gp = reinterpret_cast<const float* const*>(
+        recs + (size_t)srec[lo] * PS_REC_UNIT + sizeof(PsBlockRec));
+    sptr[i] = gp[i - ps[lo]];
+  }
   __syncthreads();
 
   for (uint32_t q = tid; q < quads; q += PS_WG) {
@@ -251,9 +213,39 @@ __global__ __launch_bounds__(PS_WG) void ps_agg_small(const PsBlockDesc* __restr
       const uint32_t mid = (lo + hi) >> 1;
       if (qs[mid] <= q) lo = mid; else hi = mid;
     }
-    const PsBlockDesc& d = sd[lo];
+    const PsBlockRec& d = sd[lo];
+    const float* const* gp = sptr + ps[lo];
     const uint32_t e = (q - qs[lo]) * 4;
-    qpart[q] = quad_any<FMA>(gptr + d.gofs, d.W, d.p, d.v, d.lr, d.mu, d.wd, e, d.n - e);
+    const uint32_t rem = d.n - e;
+    const uint32_t nw = d.W;
+    const float lr = d.lr, mu = d.mu, wd = d.wd;
+    double a = 0.0;
+    if (rem >= 4) {
+      f32x4 s = gload4(gp[0] + e);
+      uint32_t w = 1;
+      for (; w + 4 <= nw; w += 4) {  // four loads in flight, added in worker order
+        const f32x4 x0 = gload4(gp[w] + e), x1 = gload4(gp[w + 1] + e);
+        const f32x4 x2 = gload4(gp[w + 2] + e), x3 = gload4(gp[w + 3] + e);
+        s = s + x0; s = s + x1; s = s + x2; s = s + x3;
+      }
+      for (; w < nw; ++w) s = s + gload4(gp[w] + e);
+      f32x4 pp = gload4(d.p + e), vv = gload4(d.v + e);
+      a = update4<FMA>(s, pp, vv, lr, mu, wd, a);
+      __builtin_nontemporal_store(pp, reinterpret_cast<f32x4*>(d.p + e));
+      __builtin_nontemporal_store(vv, reinterpret_cast<f32x4*>(d.v + e));
+    } else {
+      for (uint32_t k = 0; k < rem; ++k) {
+        float s = gp[0][e + k];
+        for (uint32_t w = 1; w < nw; ++w) s = s + gp[w][e + k];
+        float pk = d.p[e + k], vk = d.v[e + k];
+        update1<FMA>(s, pk, vk, lr, mu, wd);
+        d.p[e + k] = pk;
+        d.v[e + k] = vk;
+        const double sdb = (double)s;
+        a = __builtin_fma(sdb, sdb, a);
+      }
+    }
+    qpart[q] = a;
   }
   __syncthreads();
 
@@ -266,21 +258,58 @@ __global__ __launch_bounds__(PS_WG) void ps_agg_small(const PsBlockDesc* __restr
   }
 }
 
+// One launch: workgroups [0, n_bins) take small-path bins, the rest take tiles
+// tile_begin .. of the large path.
+template <bool FMA>
+__global__ __launch_bounds__(PS_WG) void ps_agg_wave(const unsigned char* __restrict__ recs,
+                                                     const PsTile* __restrict__ tiles,
+                                                     uint32_t tile_begin,
+                                                     double* __restrict__ tile_part,
+                                                     const PsSmallEntry* __restrict__ entries,
+                                                     const PsBin* __restrict__ bins,
+                                                     uint32_t n_bins) {
+  const uint32_t b = blockIdx.x;
+  if (b < n_bins) {
+    small_bin<FMA>(recs, entries, bins[b]);
+  } else {
+    const uint32_t t = tile_begin + (b - n_bins);
+    large_tile<FMA>(recs, tiles[t], t, tile_part);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Telemetry of large-path blocks: one wavefront adds up a block's tile partials.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(PS_WG) void ps_block_norms(const PsBlockDesc* __restrict__ desc,
-                                                        const uint32_t* __restrict__ large_blocks,
+__global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __restrict__ recs,
+                                                        const uint32_t* __restrict__ large_recs,
                                                         uint32_t n_large,
                                                         const double* __restrict__ tile_part) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t b = blockIdx.x * (PS_WG / 64) + (threadIdx.x >> 6);
   if (b >= n_large) return;  // whole wavefront leaves together
-  const PsBlockDesc* d = desc + large_blocks[b];
+  const PsBlockRec* d =
+      reinterpret_cast<const PsBlockRec*>(recs + (size_t)large_recs[b] * PS_REC_UNIT);
   double a = 0.0;
   for (uint32_t t = lane; t < d->ntiles; t += 64) a += tile_part[d->tile0 + t];
   a = wave_sum(a);
   if (lane == 0) *d->stat = a;
+}
+
+template <bool FMA>
+void launch_agg(const PsWaveTables& t, hipStream_t stream) {
+  uint32_t bins_left = t.n_bins;
+  if (t.n_chunks == 0 && bins_left) {
+    hipLaunchKernelGGL(ps_agg_wave<FMA>, dim3(bins_left), dim3(PS_WG), 0, stream, t.recs, t.tiles, 0u,
+                       t.tile_part, t.small_entries, t.bins, bins_left);
+    return;
+  }
+  for (uint32_t c = 0; c < t.n_chunks; ++c) {
+    const uint32_t nt = t.chunks[c].end - t.chunks[c].begin;
+    // the bins ride with the first launch so that they overlap with tile work
+    hipLaunchKernelGGL(ps_agg_wave<FMA>, dim3(nt + bins_left), dim3(PS_WG), 0, stream, t.recs, t.tiles,
+                       t.chunks[c].begin, t.tile_part, t.small_entries, t.bins, bins_left);
+    bins_left = 0;
+  }
 }
 
 }  // namespace
@@ -291,29 +320,13 @@ int ps_launch_wave(const PsWaveTables& t, void* stream_) {
     if (t.ev[i]) (void)hipEventRecord(static_cast<hipEvent_t>(t.ev[i]), stream);
   };
   mark(0);
-  if (t.n_tiles) {
-    if (t.fp_contract)
-      hipLaunchKernelGGL(ps_agg_large<true>, dim3(t.n_tiles), dim3(PS_WG), 0, stream, t.desc, t.gptr,
-                         t.tiles, t.tile_part);
-    else
-      hipLaunchKernelGGL(ps_agg_large<false>, dim3(t.n_tiles), dim3(PS_WG), 0, stream, t.desc, t.gptr,
-                         t.tiles, t.tile_part);
-  }
+  if (t.fp_contract) launch_agg<true>(t, stream); else launch_agg<false>(t, stream);
   mark(1);
-  if (t.n_bins) {
-    if (t.fp_contract)
-      hipLaunchKernelGGL(ps_agg_small<true>, dim3(t.n_bins), dim3(PS_WG), 0, stream, t.desc, t.gptr,
-                         t.small_entries, t.bins);
-    else
-      hipLaunchKernelGGL(ps_agg_small<false>, dim3(t.n_bins), dim3(PS_WG), 0, stream, t.desc, t.gptr,
-                         t.small_entries, t.bins);
-  }
-  mark(2);
   if (t.n_large_blocks) {
     const uint32_t per = PS_WG / 64;
     hipLaunchKernelGGL(ps_block_norms, dim3((t.n_large_blocks + per - 1) / per), dim3(PS_WG), 0,
-                       stream, t.desc, t.large_blocks, t.n_large_blocks, t.tile_part);
+                       stream, t.recs, t.large_recs, t.n_large_blocks, t.tile_part);
   }
-  mark(3);
+  mark(2);
   return (int)hipGetLastError();
 }

@@ -61,18 +61,21 @@ struct Slot {
   size_t host_cap = 0, dev_cap = 0;
   hipEvent_t done = nullptr;
   bool in_flight = false;
-  hipEvent_t tev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};  // timing marks
+  hipEvent_t tev[4] = {nullptr, nullptr, nullptr, nullptr};  // timing marks
   bool timed = false;
+  int64_t launches = 0;
 };
 constexpr int kSlots = 4;
 
 struct Plan {
-  std::vector<PsBlockDesc> desc;
-  std::vector<const float*> gptr;
+  std::vector<unsigned char> recs;     // PsBlockRec + W pointers per listed block
+  std::vector<uint32_t> rec_of;        // record offset (8-byte units) per list position
+  std::vector<uint32_t> large_order;   // list positions of large-path blocks, launch order
   std::vector<PsTile> tiles;
+  std::vector<PsChunk> chunks;
   std::vector<PsSmallEntry> small_entries;
   std::vector<PsBin> bins;
-  std::vector<uint32_t> large_blocks;
+  std::vector<uint32_t> large_recs;
   ps_wave_stats stats{};
 };
 
@@ -101,8 +104,8 @@ int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (out->max_block_bytes == 0) out->max_block_bytes = PS_DEFAULT_BLOCK_BYTES;
   if (out->small_block_elems == 0) out->small_block_elems = PS_DEFAULT_SMALL_ELEMS;
   if (out->max_block_bytes % PS_ALIGN_BYTES != 0) return PS_ERR_ARG;
-  if (out->max_block_bytes / 4 > 0xFFFFFFF0ull) return PS_ERR_ARG;  // block numel is 32-bit on the GPU
-  if (out->small_block_elems > PS_BIN_MAX_QUADS * 2) return PS_ERR_ARG;
+  if (out->max_block_bytes > (1ull << 30)) return PS_ERR_ARG;  // byte offsets inside a block are 32-bit
+  if (out->small_block_elems > PS_SMALL_MAX_ELEMS) return PS_ERR_ARG;
   if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
   if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
   return PS_OK;
@@ -153,8 +156,8 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
   if (n < 0 || (n > 0 && !list)) return PS_ERR_ARG;
   if (n > 0x7FFFFFF0ll) return PS_ERR_ARG;
   Plan& P = c->plan;
-  P.desc.clear(); P.gptr.clear(); P.tiles.clear(); P.small_entries.clear();
-  P.bins.clear(); P.large_blocks.clear();
+  P.recs.clear(); P.rec_of.clear(); P.large_order.clear(); P.tiles.clear(); P.chunks.clear();
+  P.small_entries.clear(); P.bins.clear(); P.large_recs.clear();
   P.stats = ps_wave_stats{};
   const uint64_t stamp = ++c->wave_counter;
   const uint32_t small_max = c->cfg.small_block_elems;
@@ -170,7 +173,8 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     if (need_pushes && b.mask != j->full_mask) return PS_ERR_NOT_READY;
   }
 
-  P.desc.reserve(n);
+  // pass 2: one record per listed block, in list order; small blocks go to bins
+  P.rec_of.resize((size_t)n);
   PsBin bin{0, 0, 0, 0};
   auto close_bin = [&]() {
     if (bin.count) P.bins.push_back(bin);
@@ -179,39 +183,77 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
   for (int64_t i = 0; i < n; ++i) {
     Job& j = c->jobs[list[i].job];
     Block& b = j.blocks[list[i].block];
-    PsBlockDesc d{};
+    PsBlockRec d{};
     d.p = j.p ? j.p + b.flat_off : nullptr;
     d.v = j.v ? j.v + b.flat_off : nullptr;
     d.stat = j.stat ? j.stat + list[i].block : nullptr;
-    d.gofs = (uint32_t)P.gptr.size();
     d.n = (uint32_t)b.numel;
     d.W = (uint32_t)j.W;
     d.lr = j.lr; d.mu = j.mu; d.wd = j.wd;
-    for (int32_t w = 0; w < j.W; ++w) P.gptr.push_back((b.mask >> w) & 1u ? b.grad[w] : nullptr);
-    const uint32_t di = (uint32_t)P.desc.size();
+    const size_t at = P.recs.size();
+    P.rec_of[(size_t)i] = (uint32_t)(at / PS_REC_UNIT);
+    P.recs.resize(at + sizeof(PsBlockRec) + sizeof(const float*) * (size_t)j.W);
+    const float** gp = reinterpret_cast<const float**>(P.recs.data() + at + sizeof(PsBlockRec));
+    for (int32_t w = 0; w < j.W; ++w) gp[w] = (b.mask >> w) & 1u ? b.grad[w] : nullptr;
     if (d.n <= small_max) {
       const uint32_t q = (d.n + 3) / 4;
-      if (bin.count == PS_BIN_MAX_BLOCKS || bin.quads + q > PS_BIN_MAX_QUADS) close_bin();
-      P.small_entries.push_back(PsSmallEntry{di, bin.quads});
+      // a bin is closed once it gives every lane a quad, or when a table is full
+      if (bin.count && (bin.quads >= PS_WG || bin.count == PS_BIN_MAX_BLOCKS ||
+                        bin.quads + q > PS_BIN_MAX_QUADS || bin.nptrs + d.W > PS_BIN_MAX_PTRS))
+        close_bin();
+      P.small_entries.push_back(PsSmallEntry{P.rec_of[(size_t)i], bin.quads, bin.nptrs, 0});
       bin.count += 1;
       bin.quads += q;
+      bin.nptrs += d.W;
       P.stats.n_small_blocks += 1;
       P.stats.small_params += d.n;
+      P.stats.small_algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
     } else {
-      d.tile0 = (uint32_t)P.tiles.size();
-      d.ntiles = (d.n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
-      for (uint32_t t = 0; t < d.ntiles; ++t) P.tiles.push_back(PsTile{di, t * PS_TILE_ELEMS});
-      P.large_blocks.push_back(di);
+      P.large_order.push_back((uint32_t)i);
     }
-    P.desc.push_back(d);
+    std::memcpy(P.recs.data() + at, &d, sizeof(d));
     P.stats.n_params += d.n;
     P.stats.algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
-    if (d.n <= small_max) P.stats.small_algorithmic_bytes += (uint64_t)(4 * j.W + 16) * d.n;
   }
   close_bin();
+
+  // pass 3: launch order of the large path.  Blocks are independent, so any
+  // order gives the same result; tiles of one worker count are made adjacent
+  // (most workers first) and, inside a class, one job's blocks stay together,
+  // which keeps the number of HBM streams touched at any moment small.
+  std::stable_sort(P.large_order.begin(), P.large_order.end(), [&](uint32_t a, uint32_t b) {
+    const Job& ja = c->jobs[list[a].job];
+    const Job& jb = c->jobs[list[b].job];
+    if (ja.W != jb.W) return ja.W > jb.W;
+    return list[a].job < list[b].job;
+  });
+  uint32_t cur_w = 0;
+  PsChunk chunk{0, 0};
+  for (uint32_t i : P.large_order) {
+    PsBlockRec* d = reinterpret_cast<PsBlockRec*>(P.recs.data() + (size_t)P.rec_of[i] * PS_REC_UNIT);
+    d->tile0 = (uint32_t)P.tiles.size();
+    d->ntiles = (d->n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
+    if (d->W != cur_w && chunk.end > chunk.begin) {
+      P.chunks.push_back(chunk);
+      chunk.begin = chunk.end;
+    }
+    cur_w = d->W;
+    const uint32_t limit = ps_chunk_tiles(cur_w);
+    for (uint32_t t = 0; t < d->ntiles; ++t) {
+      P.tiles.push_back(PsTile{P.rec_of[i], t * PS_TILE_ELEMS});
+      if (++chunk.end - chunk.begin == limit) {
+        P.chunks.push_back(chunk);
+        chunk.begin = chunk.end;
+      }
+    }
+    P.large_recs.push_back(P.rec_of[i]);
+  }
+  if (chunk.end > chunk.begin) P.chunks.push_back(chunk);
+
   P.stats.n_blocks = n;
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
   P.stats.n_small_bins = (int64_t)P.bins.size();
+  P.stats.n_launches = (int64_t)std::max<size_t>(P.chunks.size(), P.bins.empty() ? 0 : 1);
   return PS_OK;
 }
 
@@ -222,15 +264,15 @@ int32_t slot_retire(ps_ctx* c, Slot& s) {
   s.in_flight = false;
   if (s.timed) {
     s.timed = false;
-    float ms[4] = {0, 0, 0, 0};
-    for (int i = 0; i < 4; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], s.tev[i], s.tev[i + 1]));
+    float ms[3] = {0, 0, 0};
+    for (int i = 0; i < 3; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], s.tev[i], s.tev[i + 1]));
     float tot = 0;
-    PS_HIP(c, hipEventElapsedTime(&tot, s.tev[0], s.tev[4]));
+    PS_HIP(c, hipEventElapsedTime(&tot, s.tev[0], s.tev[3]));
     c->timing.n_waves += 1;
+    c->timing.n_launches += s.launches;
     c->timing.upload_ms += ms[0];
-    c->timing.large_ms += ms[1];
-    c->timing.small_ms += ms[2];
-    c->timing.norms_ms += ms[3];
+    c->timing.agg_ms += ms[1];
+    c->timing.norms_ms += ms[2];
     c->timing.total_ms += tot;
   }
   return PS_OK;
@@ -543,12 +585,11 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   Plan& P = c->plan;
 
   size_t cur = 0;
-  const size_t o_desc = place<PsBlockDesc>(&cur, P.desc.size());
-  const size_t o_gptr = place<const float*>(&cur, P.gptr.size());
+  const size_t o_recs = place<unsigned char>(&cur, P.recs.size());
   const size_t o_tiles = place<PsTile>(&cur, P.tiles.size());
   const size_t o_small = place<PsSmallEntry>(&cur, P.small_entries.size());
   const size_t o_bins = place<PsBin>(&cur, P.bins.size());
-  const size_t o_large = place<uint32_t>(&cur, P.large_blocks.size());
+  const size_t o_large = place<uint32_t>(&cur, P.large_recs.size());
   const size_t upload = cur;
   const size_t o_part = place<double>(&cur, P.tiles.size());
   const size_t dev_total = cur;
@@ -558,38 +599,39 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   st = slot_reserve(c, s, upload, dev_total);
   if (st != PS_OK) return st;
   auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(s.host + at, src, bytes); };
-  put(o_desc, P.desc.data(), P.desc.size() * sizeof(PsBlockDesc));
-  put(o_gptr, P.gptr.data(), P.gptr.size() * sizeof(const float*));
+  put(o_recs, P.recs.data(), P.recs.size());
   put(o_tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
   put(o_small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
   put(o_bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
-  put(o_large, P.large_blocks.data(), P.large_blocks.size() * sizeof(uint32_t));
+  put(o_large, P.large_recs.data(), P.large_recs.size() * sizeof(uint32_t));
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
   PsWaveTables t{};
   if (c->timing_on) {
-    for (int i = 0; i < 5; ++i)
+    for (int i = 0; i < 4; ++i)
       if (!s.tev[i]) PS_HIP(c, hipEventCreate(&s.tev[i]));
     PS_HIP(c, hipEventRecord(s.tev[0], hs));
-    for (int i = 0; i < 4; ++i) t.ev[i] = s.tev[i + 1];
+    for (int i = 0; i < 3; ++i) t.ev[i] = s.tev[i + 1];
   }
   PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
-  t.desc = reinterpret_cast<const PsBlockDesc*>(s.dev + o_desc);
-  t.gptr = reinterpret_cast<const float* const*>(s.dev + o_gptr);
+  t.recs = reinterpret_cast<const unsigned char*>(s.dev + o_recs);
   t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
   t.n_tiles = (uint32_t)P.tiles.size();
+  t.chunks = P.chunks.data();
+  t.n_chunks = (uint32_t)P.chunks.size();
   t.tile_part = reinterpret_cast<double*>(s.dev + o_part);
   t.small_entries = reinterpret_cast<const PsSmallEntry*>(s.dev + o_small);
   t.bins = reinterpret_cast<const PsBin*>(s.dev + o_bins);
   t.n_bins = (uint32_t)P.bins.size();
-  t.large_blocks = reinterpret_cast<const uint32_t*>(s.dev + o_large);
-  t.n_large_blocks = (uint32_t)P.large_blocks.size();
+  t.large_recs = reinterpret_cast<const uint32_t*>(s.dev + o_large);
+  t.n_large_blocks = (uint32_t)P.large_recs.size();
   t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
   const int le = ps_launch_wave(t, stream);
   if (le != 0) return hip_fail(c, (hipError_t)le, "launching the wave");
   PS_HIP(c, hipEventRecord(s.done, hs));
   s.in_flight = true;
   s.timed = c->timing_on;
+  s.launches = P.stats.n_launches;
 
   // the wave is enqueued: consume the pushes
   for (int64_t i = 0; i < n; ++i) {
