@@ -85,6 +85,10 @@ typedef struct ps_config {
                                  packing work, anything touching the device returns
                                  PS_ERR_NO_DEVICE */
   uint64_t arena_bytes;
+  uint32_t launch_tiles;      /* tiles (4096 values each) per kernel launch of the large-block
+                                 path; 0 = chosen by worker count (1024 .. 3072).  A launch this
+                                 size is resident on the chip all at once. */
+  uint32_t reserved_;         /* must be 0 */
 } ps_config;
 
 typedef struct ps_block_ref {

@@ -33,7 +33,8 @@ class PsError(RuntimeError):
 
 class Config(C.Structure):
     _fields_ = [("max_block_bytes", C.c_uint64), ("small_block_elems", C.c_uint32),
-                ("flags", C.c_uint32), ("arena_dev", C.c_void_p), ("arena_bytes", C.c_uint64)]
+                ("flags", C.c_uint32), ("arena_dev", C.c_void_p), ("arena_bytes", C.c_uint64),
+                ("launch_tiles", C.c_uint32), ("reserved_", C.c_uint32)]
 
 
 class BlockRef(C.Structure):
@@ -148,12 +149,13 @@ class ParameterService:
     service carves master copies from (None = planning context, no device)."""
 
     def __init__(self, arena: Optional[torch.Tensor] = None, max_block_bytes: int = 0,
-                 small_block_elems: int = 0, flags: int = 0):
+                 small_block_elems: int = 0, flags: int = 0, launch_tiles: int = 0):
         self.L = load_library()
         self.arena = arena
         cfg = Config(max_block_bytes, small_block_elems, flags,
                      arena.data_ptr() if arena is not None else None,
-                     arena.numel() * arena.element_size() if arena is not None else 0)
+                     arena.numel() * arena.element_size() if arena is not None else 0,
+                     launch_tiles, 0)
         self.cfg = cfg
         self.ctx = C.c_void_p()
         self._check(self.L.ps_create(C.byref(cfg), C.byref(self.ctx)))
@@ -170,7 +172,7 @@ class ParameterService:
     @staticmethod
     def job_arena_bytes(layer_numel: Sequence[int], max_block_bytes: int = 0) -> int:
         L = load_library()
-        cfg = Config(max_block_bytes, 0, 0, None, 0)
+        cfg = Config(max_block_bytes, 0, 0, None, 0, 0, 0)
         arr = (C.c_int64 * len(layer_numel))(*layer_numel)
         out = C.c_uint64()
         st = L.ps_job_arena_bytes(C.byref(cfg), arr, len(layer_numel), C.byref(out))

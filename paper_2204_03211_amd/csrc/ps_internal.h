@@ -46,9 +46,11 @@ struct PsBin {
   uint32_t nptrs;   // gradient pointers of all entries together (<= PS_BIN_MAX_PTRS)
 };
 
-// A contiguous run of tiles launched as one kernel.
+// A contiguous run of tiles, all of blocks with the same worker count W,
+// launched as one kernel.
 struct PsChunk {
   uint32_t begin, end;
+  uint32_t W;
 };
 
 constexpr uint32_t PS_WG = 256;                 // threads per workgroup (4 wavefronts)
@@ -63,7 +65,10 @@ constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path 
 // launch are resident together, start together and therefore reach their
 // stores at about the same time, which keeps HBM reads and writes from
 // interleaving finely; the more read streams a tile has, the more that matters.
-inline uint32_t ps_chunk_tiles(uint32_t W) { return W >= 12 ? 1024u : (W >= 6 ? 1536u : 2048u); }
+// The counts are the best of a sweep on MI355X (uniform 2^20-element blocks).
+inline uint32_t ps_chunk_tiles(uint32_t W) {
+  return W >= 12 ? 1024u : (W >= 6 ? 1536u : (W >= 3 ? 2560u : 3072u));
+}
 
 struct PsWaveTables {
   const unsigned char* recs;     // PsBlockRec records

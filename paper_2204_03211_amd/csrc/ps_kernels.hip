@@ -128,7 +128,7 @@ __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
   return a;
 }
 
-template <bool FMA>
+template <int W, bool FMA>
 __device__ __forceinline__ void large_tile(const unsigned char* __restrict__ recs, PsTile te,
                                            uint32_t slot, double* __restrict__ tile_part) {
   const uint32_t tid = threadIdx.x;
@@ -137,19 +137,10 @@ __device__ __forceinline__ void large_tile(const unsigned char* __restrict__ rec
   const PsBlockRec* __restrict__ r =
       reinterpret_cast<const PsBlockRec*>(recs + (size_t)ro * PS_REC_UNIT);
   const float* const* __restrict__ gp = reinterpret_cast<const float* const*>(r + 1);
-  const uint32_t W = r->W;
   const uint32_t left = r->n - off;
   const uint32_t bytes = (left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
 
-  double a;
-  switch (W) {
-    case 1: a = tile_body<1, FMA>(r, gp, 1, off, bytes, tid); break;
-    case 2: a = tile_body<2, FMA>(r, gp, 2, off, bytes, tid); break;
-    case 4: a = tile_body<4, FMA>(r, gp, 4, off, bytes, tid); break;
-    case 8: a = tile_body<8, FMA>(r, gp, 8, off, bytes, tid); break;
-    case 16: a = tile_body<16, FMA>(r, gp, 16, off, bytes, tid); break;
-    default: a = tile_body<0, FMA>(r, gp, W, off, bytes, tid); break;
-  }
+  double a = tile_body<W, FMA>(r, gp, r->W, off, bytes, tid);
 
   a = wave_sum(a);
   __shared__ double red[PS_WG / 64];
@@ -258,10 +249,15 @@ __device__ __forceinline__ void small_bin(const unsigned char* __restrict__ recs
   }
 }
 
+#ifndef PS_MIN_WAVES
+#define PS_MIN_WAVES 1
+#endif
 // One launch: workgroups [0, n_bins) take small-path bins, the rest take tiles
-// tile_begin .. of the large path.
-template <bool FMA>
-__global__ __launch_bounds__(PS_WG) void ps_agg_wave(const unsigned char* __restrict__ recs,
+// tile_begin .. of the large path.  All tiles of one launch belong to blocks with
+// the same worker count; W > 0 names it at compile time (every gradient load of
+// a tile is then issued before the first add), W == 0 reads it from the record.
+template <int W, bool FMA>
+__global__ __launch_bounds__(PS_WG, PS_MIN_WAVES) void ps_agg_wave(const unsigned char* __restrict__ recs,
                                                      const PsTile* __restrict__ tiles,
                                                      uint32_t tile_begin,
                                                      double* __restrict__ tile_part,
@@ -273,7 +269,7 @@ __global__ __launch_bounds__(PS_WG) void ps_agg_wave(const unsigned char* __rest
     small_bin<FMA>(recs, entries, bins[b]);
   } else {
     const uint32_t t = tile_begin + (b - n_bins);
-    large_tile<FMA>(recs, tiles[t], t, tile_part);
+    large_tile<W, FMA>(recs, tiles[t], t, tile_part);
   }
 }
 
@@ -295,19 +291,32 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
   if (lane == 0) *d->stat = a;
 }
 
+template <int W, bool FMA>
+void launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
+                uint32_t n_bins) {
+  hipLaunchKernelGGL((ps_agg_wave<W, FMA>), dim3(n_tiles + n_bins), dim3(PS_WG), 0, stream, t.recs,
+                     t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins);
+}
+
 template <bool FMA>
 void launch_agg(const PsWaveTables& t, hipStream_t stream) {
   uint32_t bins_left = t.n_bins;
   if (t.n_chunks == 0 && bins_left) {
-    hipLaunchKernelGGL(ps_agg_wave<FMA>, dim3(bins_left), dim3(PS_WG), 0, stream, t.recs, t.tiles, 0u,
-                       t.tile_part, t.small_entries, t.bins, bins_left);
+    launch_one<0, FMA>(t, stream, 0, 0, bins_left);
     return;
   }
   for (uint32_t c = 0; c < t.n_chunks; ++c) {
-    const uint32_t nt = t.chunks[c].end - t.chunks[c].begin;
+    const PsChunk& ch = t.chunks[c];
+    const uint32_t nt = ch.end - ch.begin;
     // the bins ride with the first launch so that they overlap with tile work
-    hipLaunchKernelGGL(ps_agg_wave<FMA>, dim3(nt + bins_left), dim3(PS_WG), 0, stream, t.recs, t.tiles,
-                       t.chunks[c].begin, t.tile_part, t.small_entries, t.bins, bins_left);
+    switch (ch.W) {
+      case 1: launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      case 2: launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      case 4: launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      case 8: launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      case 16: launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      default: launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left); break;
+    }
     bins_left = 0;
   }
 }

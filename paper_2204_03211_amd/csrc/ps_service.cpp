@@ -107,6 +107,7 @@ int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (out->max_block_bytes > (1ull << 30)) return PS_ERR_ARG;  // byte offsets inside a block are 32-bit
   if (out->small_block_elems > PS_SMALL_MAX_ELEMS) return PS_ERR_ARG;
   if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
+  if (out->reserved_ != 0) return PS_ERR_ARG;
   if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
   return PS_OK;
 }
@@ -228,7 +229,7 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     return list[a].job < list[b].job;
   });
   uint32_t cur_w = 0;
-  PsChunk chunk{0, 0};
+  PsChunk chunk{0, 0, 0};
   for (uint32_t i : P.large_order) {
     PsBlockRec* d = reinterpret_cast<PsBlockRec*>(P.recs.data() + (size_t)P.rec_of[i] * PS_REC_UNIT);
     d->tile0 = (uint32_t)P.tiles.size();
@@ -238,7 +239,8 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
       chunk.begin = chunk.end;
     }
     cur_w = d->W;
-    const uint32_t limit = ps_chunk_tiles(cur_w);
+    chunk.W = cur_w;
+    const uint32_t limit = c->cfg.launch_tiles ? c->cfg.launch_tiles : ps_chunk_tiles(cur_w);
     for (uint32_t t = 0; t < d->ntiles; ++t) {
       P.tiles.push_back(PsTile{P.rec_of[i], t * PS_TILE_ELEMS});
       if (++chunk.end - chunk.begin == limit) {
