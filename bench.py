@@ -101,7 +101,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
-              "and no multi-GPU path exists (see DESIGN.md, 'More than one GPU').", file=sys.stderr)
+              "and no multi-GPU path exists; run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch
