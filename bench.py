@@ -98,6 +98,7 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
+    ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
@@ -121,7 +122,8 @@ def main() -> int:
         return 0
     specs, seed = specs_for(args.workload)
     t_setup = time.perf_counter()
-    gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles)
+    gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
+                     store_hold_permille=args.hold_permille)
     gpu.fill_grads(0)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup

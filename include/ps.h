@@ -86,9 +86,13 @@ typedef struct ps_config {
                                  PS_ERR_NO_DEVICE */
   uint64_t arena_bytes;
   uint32_t launch_tiles;      /* tiles (4096 values each) per kernel launch of the large-block
-                                 path; 0 = chosen by worker count (1024 .. 3072).  A launch this
-                                 size is resident on the chip all at once. */
-  uint32_t reserved_;         /* must be 0 */
+                                 path; 0 = chosen by worker count (1024 or 1536), never more
+                                 than fit on the chip at once */
+  int32_t store_hold_permille; /* a launch's workgroups keep their results in registers and
+                                 store them only once this fraction (in 1/1000) of the
+                                 launch's predicted read time has passed since they
+                                 started, so that reads and writes reach HBM in separate
+                                 bursts; 0 = default (900), negative = no hold, at most 2000 */
 } ps_config;
 
 typedef struct ps_block_ref {

@@ -34,7 +34,7 @@ class PsError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [("max_block_bytes", C.c_uint64), ("small_block_elems", C.c_uint32),
                 ("flags", C.c_uint32), ("arena_dev", C.c_void_p), ("arena_bytes", C.c_uint64),
-                ("launch_tiles", C.c_uint32), ("reserved_", C.c_uint32)]
+                ("launch_tiles", C.c_uint32), ("store_hold_permille", C.c_int32)]
 
 
 class BlockRef(C.Structure):
@@ -149,13 +149,14 @@ class ParameterService:
     service carves master copies from (None = planning context, no device)."""
 
     def __init__(self, arena: Optional[torch.Tensor] = None, max_block_bytes: int = 0,
-                 small_block_elems: int = 0, flags: int = 0, launch_tiles: int = 0):
+                 small_block_elems: int = 0, flags: int = 0, launch_tiles: int = 0,
+                 store_hold_permille: int = 0):
         self.L = load_library()
         self.arena = arena
         cfg = Config(max_block_bytes, small_block_elems, flags,
                      arena.data_ptr() if arena is not None else None,
                      arena.numel() * arena.element_size() if arena is not None else 0,
-                     launch_tiles, 0)
+                     launch_tiles, store_hold_permille)
         self.cfg = cfg
         self.ctx = C.c_void_p()
         self._check(self.L.ps_create(C.byref(cfg), C.byref(self.ctx)))

@@ -51,24 +51,36 @@ struct PsBin {
 struct PsChunk {
   uint32_t begin, end;
   uint32_t W;
+  uint32_t hold_ticks;  // wall-clock ticks a workgroup keeps its results before storing them
+  uint64_t read_bytes;  // bytes the launch reads: sum over its tiles of (4W + 8) * elements
 };
 
 constexpr uint32_t PS_WG = 256;                 // threads per workgroup (4 wavefronts)
-constexpr uint32_t PS_TILE_QUADS_PER_LANE = 4;  // 16-byte accesses per lane per stream in a tile
-constexpr uint32_t PS_TILE_ELEMS = PS_WG * 4 * PS_TILE_QUADS_PER_LANE;  // 4096
+#ifndef PS_TILE_U
+#define PS_TILE_U 4
+#endif
+#ifndef PS_LOAD_G
+#define PS_LOAD_G 3
+#endif
+constexpr uint32_t PS_TILE_QUADS_PER_LANE = PS_TILE_U;  // 16-byte accesses per lane per stream in a tile
+constexpr uint32_t PS_TILE_ELEMS = PS_WG * 4 * PS_TILE_QUADS_PER_LANE;
 constexpr uint32_t PS_BIN_MAX_BLOCKS = 64;
 constexpr uint32_t PS_BIN_MAX_QUADS = 1024;  // >= quads of the largest small-path block
 constexpr uint32_t PS_BIN_MAX_PTRS = 1024;
 constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path accepts
 
-// Tiles per launch of the large path, by worker count.  All workgroups of one
-// launch are resident together, start together and therefore reach their
-// stores at about the same time, which keeps HBM reads and writes from
-// interleaving finely; the more read streams a tile has, the more that matters.
-// The counts are the best of a sweep on MI355X (uniform 2^20-element blocks).
-inline uint32_t ps_chunk_tiles(uint32_t W) {
-  return W >= 12 ? 1024u : (W >= 6 ? 1536u : (W >= 3 ? 2560u : 3072u));
-}
+// Tiles per launch of the large path, by worker count.  HBM serves pure reads
+// and pure writes much faster than a fine interleaving of many read streams with
+// a few write streams, so a wave is cut into launches small enough to be resident
+// on the chip all at once: their workgroups start together, read together, keep
+// their results in registers until most of the launch's reads are done
+// (hold_ticks) and then write together.
+inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e. whatever is resident
+
+// Sustained pure-read HBM rate measured on MI355X (16-byte non-temporal buffer
+// loads, many streams); used only to predict when a launch's reads end.
+constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
+constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 1000;
 
 struct PsWaveTables {
   const unsigned char* recs;     // PsBlockRec records
@@ -87,6 +99,10 @@ struct PsWaveTables {
   // aggregation launches, and after the telemetry reduction (NULL = no timing)
   void* ev[3];
 };
+
+// Workgroups of the aggregation kernel for worker count W that the current
+// device holds at once; 0 if it cannot be queried.
+uint32_t ps_resident_workgroups(uint32_t W);
 
 // Enqueue the kernels of one wave on stream (a hipStream_t).  Returns a
 // hipError_t value (0 = success).

@@ -87,8 +87,10 @@ __device__ __forceinline__ double wave_sum(double a) {
 template <int W, bool FMA>
 __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
                                             const float* const* __restrict__ gp, uint32_t w_rt,
-                                            uint32_t off, uint32_t bytes, uint32_t tid) {
+                                            uint32_t off, uint32_t bytes, uint32_t tid,
+                                            unsigned long long t_start, uint32_t hold_ticks) {
   constexpr int U = PS_TILE_QUADS_PER_LANE;
+  constexpr int G = PS_LOAD_G;  // workers whose loads are in flight together (bounds VGPR use)
   const float lr = r->lr, mu = r->mu, wd = r->wd;
   f32x4 acc[U];
   {
@@ -98,10 +100,23 @@ __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
   }
   if constexpr (W > 0) {
 #pragma unroll
-    for (int w = 1; w < W; ++w) {
-      const __amdgpu_buffer_rsrc_t gw = span(gp[w] + off, bytes);
+    for (int w0 = 1; w0 < W; w0 += G) {
+      f32x4 x[G][U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) acc[u] = acc[u] + load4(gw, (u * PS_WG + tid) * 16);
+      for (int g = 0; g < G; ++g)
+        if (w0 + g < W) {
+          const __amdgpu_buffer_rsrc_t gw = span(gp[w0 + g] + off, bytes);
+#pragma unroll
+          for (int u = 0; u < U; ++u) x[g][u] = load4(gw, (u * PS_WG + tid) * 16);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        if (w0 + g < W) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) acc[u] = acc[u] + x[g][u];  // worker order: w0, w0+1, ...
+        }
+      __builtin_amdgcn_sched_barrier(0);
     }
   } else {
     for (uint32_t w = 1; w < w_rt; ++w) {
@@ -120,6 +135,12 @@ __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
   double a = 0.0;
 #pragma unroll
   for (int u = 0; u < U; ++u) a = update4<FMA>(acc[u], pp[u], vv[u], lr, mu, wd, a);
+  // The results now sit in registers.  Every workgroup of the launch started at
+  // about t_start; waiting until hold_ticks later lets the launch's reads drain
+  // before its writes begin.  The clock always advances, so the wait ends.
+#pragma unroll
+  for (int u = 0; u < U; ++u) asm volatile("" : "+v"(pp[u]), "+v"(vv[u]));  // no sinking past the wait
+  while ((uint32_t)(wall_clock64() - t_start) < hold_ticks) __builtin_amdgcn_s_sleep(8);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     store4(rp, (u * PS_WG + tid) * 16, pp[u]);
@@ -130,7 +151,9 @@ __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
 
 template <int W, bool FMA>
 __device__ __forceinline__ void large_tile(const unsigned char* __restrict__ recs, PsTile te,
-                                           uint32_t slot, double* __restrict__ tile_part) {
+                                           uint32_t slot, double* __restrict__ tile_part,
+                                           uint32_t hold_ticks) {
+  const unsigned long long t_start = wall_clock64();
   const uint32_t tid = threadIdx.x;
   const uint32_t ro = __builtin_amdgcn_readfirstlane(te.rec);
   const uint32_t off = __builtin_amdgcn_readfirstlane(te.off);
@@ -140,7 +163,7 @@ __device__ __forceinline__ void large_tile(const unsigned char* __restrict__ rec
   const uint32_t left = r->n - off;
   const uint32_t bytes = (left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
 
-  double a = tile_body<W, FMA>(r, gp, r->W, off, bytes, tid);
+  double a = tile_body<W, FMA>(r, gp, r->W, off, bytes, tid, t_start, hold_ticks);
 
   a = wave_sum(a);
   __shared__ double red[PS_WG / 64];
@@ -263,13 +286,13 @@ __global__ __launch_bounds__(PS_WG, PS_MIN_WAVES) void ps_agg_wave(const unsigne
                                                      double* __restrict__ tile_part,
                                                      const PsSmallEntry* __restrict__ entries,
                                                      const PsBin* __restrict__ bins,
-                                                     uint32_t n_bins) {
+                                                     uint32_t n_bins, uint32_t hold_ticks) {
   const uint32_t b = blockIdx.x;
   if (b < n_bins) {
     small_bin<FMA>(recs, entries, bins[b]);
   } else {
     const uint32_t t = tile_begin + (b - n_bins);
-    large_tile<W, FMA>(recs, tiles[t], t, tile_part);
+    large_tile<W, FMA>(recs, tiles[t], t, tile_part, hold_ticks);
   }
 }
 
@@ -293,16 +316,16 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
 
 template <int W, bool FMA>
 void launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
-                uint32_t n_bins) {
+                uint32_t n_bins, uint32_t hold_ticks) {
   hipLaunchKernelGGL((ps_agg_wave<W, FMA>), dim3(n_tiles + n_bins), dim3(PS_WG), 0, stream, t.recs,
-                     t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins);
+                     t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins, hold_ticks);
 }
 
 template <bool FMA>
 void launch_agg(const PsWaveTables& t, hipStream_t stream) {
   uint32_t bins_left = t.n_bins;
   if (t.n_chunks == 0 && bins_left) {
-    launch_one<0, FMA>(t, stream, 0, 0, bins_left);
+    launch_one<0, FMA>(t, stream, 0, 0, bins_left, 0);
     return;
   }
   for (uint32_t c = 0; c < t.n_chunks; ++c) {
@@ -310,18 +333,41 @@ void launch_agg(const PsWaveTables& t, hipStream_t stream) {
     const uint32_t nt = ch.end - ch.begin;
     // the bins ride with the first launch so that they overlap with tile work
     switch (ch.W) {
-      case 1: launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left); break;
-      case 2: launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left); break;
-      case 4: launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left); break;
-      case 8: launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left); break;
-      case 16: launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left); break;
-      default: launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left); break;
+      case 1: launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 2: launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 4: launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 8: launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 16: launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      default: launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
     }
     bins_left = 0;
   }
 }
 
 }  // namespace
+
+template <int W>
+static uint32_t resident_of(int cus) {
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ps_agg_wave<W, false>, PS_WG, 0) != hipSuccess)
+    return 0;
+  return per_cu > 0 ? (uint32_t)(per_cu * cus) : 0;
+}
+
+uint32_t ps_resident_workgroups(uint32_t W) {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+    return 0;
+  switch (W) {
+    case 1: return resident_of<1>(cus);
+    case 2: return resident_of<2>(cus);
+    case 4: return resident_of<4>(cus);
+    case 8: return resident_of<8>(cus);
+    case 16: return resident_of<16>(cus);
+    default: return resident_of<0>(cus);
+  }
+}
 
 int ps_launch_wave(const PsWaveTables& t, void* stream_) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);

@@ -94,6 +94,8 @@ struct ps_ctx {
   std::string last_error;
   bool timing_on = false;
   ps_timing timing{};
+  double clock_hz = 1.0e8;      // rate of the device's wall clock
+  uint32_t resident_tiles[PS_MAX_W + 1] = {};  // per W: workgroups the chip holds at once (0 = unknown)
 };
 
 namespace {
@@ -107,7 +109,7 @@ int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (out->max_block_bytes > (1ull << 30)) return PS_ERR_ARG;  // byte offsets inside a block are 32-bit
   if (out->small_block_elems > PS_SMALL_MAX_ELEMS) return PS_ERR_ARG;
   if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
-  if (out->reserved_ != 0) return PS_ERR_ARG;
+  if (out->store_hold_permille > 2000) return PS_ERR_ARG;
   if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
   return PS_OK;
 }
@@ -229,7 +231,7 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     return list[a].job < list[b].job;
   });
   uint32_t cur_w = 0;
-  PsChunk chunk{0, 0, 0};
+  PsChunk chunk{0, 0, 0, 0, 0};
   for (uint32_t i : P.large_order) {
     PsBlockRec* d = reinterpret_cast<PsBlockRec*>(P.recs.data() + (size_t)P.rec_of[i] * PS_REC_UNIT);
     d->tile0 = (uint32_t)P.tiles.size();
@@ -237,20 +239,32 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     if (d->W != cur_w && chunk.end > chunk.begin) {
       P.chunks.push_back(chunk);
       chunk.begin = chunk.end;
+      chunk.read_bytes = 0;
     }
     cur_w = d->W;
     chunk.W = cur_w;
-    const uint32_t limit = c->cfg.launch_tiles ? c->cfg.launch_tiles : ps_chunk_tiles(cur_w);
+    uint32_t limit = c->cfg.launch_tiles ? c->cfg.launch_tiles : ps_chunk_tiles(cur_w);
+    if (c->resident_tiles[cur_w] && limit > c->resident_tiles[cur_w]) limit = c->resident_tiles[cur_w];
+    // the first launch also carries the small-path bins: leave them room
+    if (P.chunks.empty() && limit > 2 * P.bins.size()) limit -= (uint32_t)P.bins.size();
     for (uint32_t t = 0; t < d->ntiles; ++t) {
       P.tiles.push_back(PsTile{P.rec_of[i], t * PS_TILE_ELEMS});
-      if (++chunk.end - chunk.begin == limit) {
+      const uint32_t len = std::min<uint32_t>(PS_TILE_ELEMS, d->n - t * PS_TILE_ELEMS);
+      chunk.read_bytes += (uint64_t)(4 * cur_w + 8) * len;
+      if (++chunk.end - chunk.begin >= limit) {
         P.chunks.push_back(chunk);
         chunk.begin = chunk.end;
+        chunk.read_bytes = 0;
       }
     }
     P.large_recs.push_back(P.rec_of[i]);
   }
   if (chunk.end > chunk.begin) P.chunks.push_back(chunk);
+  // when each launch's reads are expected to be over, in wall-clock ticks
+  const int32_t pm = c->cfg.store_hold_permille;
+  const double frac = pm < 0 ? 0.0 : (pm == 0 ? PS_DEFAULT_HOLD_PERMILLE : pm) / 1000.0;
+  for (PsChunk& ch : P.chunks)
+    ch.hold_ticks = (uint32_t)(frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz);
 
   P.stats.n_blocks = n;
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
@@ -347,6 +361,13 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) {
   if (!c) return PS_ERR_NOMEM;
   c->cfg = n;
   c->cap_elems = (int64_t)(n.max_block_bytes / 4);
+  if (n.arena_dev) {
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+      c->clock_hz = 1000.0 * khz;
+    for (uint32_t w = 0; w <= PS_MAX_W; ++w) c->resident_tiles[w] = ps_resident_workgroups(w);
+  }
   *out_ctx = c;
   return PS_OK;
 }

@@ -160,7 +160,7 @@ def test_argument_errors_and_unregister():
     ctx = C.c_void_p()
     for cfg in (Config(1000, 0, 0, None, 0, 0, 0), Config(0, 5000, 0, None, 0, 0, 0),
                 Config(0, 0, 8, None, 0, 0, 0), Config(0, 0, 0, 128, 1 << 20, 0, 0),
-                Config(2 << 30, 0, 0, None, 0, 0, 0), Config(0, 0, 0, None, 0, 0, 1)):
+                Config(2 << 30, 0, 0, None, 0, 0, 0), Config(0, 0, 0, None, 0, 0, 2001)):
         assert L.ps_create(C.byref(cfg), C.byref(ctx)) == -1
     svc = ParameterService(None)
     for layers, W, lr in [([0], 2, 0.1), ([10], 0, 0.1), ([10], 33, 0.1), ([], 2, 0.1),
