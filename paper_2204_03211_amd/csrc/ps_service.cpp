@@ -54,20 +54,16 @@ struct Job {
   int64_t* stat_round = nullptr; // host only
 };
 
-// Device + pinned-host buffers for the tables of one in-flight wave.
-struct Slot {
-  char* host = nullptr;
-  char* dev = nullptr;
-  size_t host_cap = 0, dev_cap = 0;
-  hipEvent_t done = nullptr;
-  bool in_flight = false;
-  hipEvent_t tev[4] = {nullptr, nullptr, nullptr, nullptr};  // timing marks
-  bool timed = false;
+// HIP events bracketing the phases of one measured wave.
+struct TimingSet {
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  bool pending = false;
   int64_t launches = 0;
 };
-constexpr int kSlots = 4;
+constexpr int kTimingSets = 8;
 
 struct Plan {
+  std::vector<uint64_t> sig;           // what the tables depend on: the list and its gradient pointers
   std::vector<unsigned char> recs;     // PsBlockRec + W pointers per listed block
   std::vector<uint32_t> rec_of;        // record offset (8-byte units) per list position
   std::vector<uint32_t> large_order;   // list positions of large-path blocks, launch order
@@ -78,6 +74,22 @@ struct Plan {
   std::vector<uint32_t> large_recs;
   ps_wave_stats stats{};
 };
+
+// Device + pinned-host buffers holding the tables of one wave, and the host
+// side of that wave's plan.  A slot whose plan matches the next call is reused
+// without rebuilding or uploading anything.
+struct Slot {
+  char* host = nullptr;
+  char* dev = nullptr;
+  size_t host_cap = 0, dev_cap = 0;
+  hipEvent_t done = nullptr;
+  bool in_flight = false;
+  hipStream_t stream = nullptr;  // stream of the wave that last used the slot
+  bool valid = false;            // plan and device tables are in step
+  Plan plan;
+  PsWaveTables tables{};
+};
+constexpr int kSlots = 4;
 
 }  // namespace
 
@@ -90,7 +102,11 @@ struct ps_ctx {
   uint64_t wave_counter = 0;
   Slot slots[kSlots];
   int next_slot = 0;
-  Plan plan;
+  int last_slot = -1;            // slot of the most recent wave (candidate for reuse)
+  TimingSet tsets[kTimingSets];
+  int next_tset = 0;
+  Plan plan;                     // scratch of ps_plan_wave
+  std::vector<uint64_t> sig;     // scratch: signature of the list being validated
   std::string last_error;
   bool timing_on = false;
   ps_timing timing{};
@@ -153,19 +169,13 @@ int32_t hip_fail(ps_ctx* c, hipError_t e, const char* what) {
     if (e_ != hipSuccess) return hip_fail(c, e_, #call); \
   } while (0)
 
-// Validate a block list and lay out the tables of its wave in c->plan.
-// Changes nothing but c->plan, c->wave_counter and the blocks' duplicate stamps.
-int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pushes) {
+// Validate a block list; gather into c->sig what a plan for it depends on.
+// Changes nothing else but c->wave_counter and the blocks' duplicate stamps.
+int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pushes) {
   if (n < 0 || (n > 0 && !list)) return PS_ERR_ARG;
   if (n > 0x7FFFFFF0ll) return PS_ERR_ARG;
-  Plan& P = c->plan;
-  P.recs.clear(); P.rec_of.clear(); P.large_order.clear(); P.tiles.clear(); P.chunks.clear();
-  P.small_entries.clear(); P.bins.clear(); P.large_recs.clear();
-  P.stats = ps_wave_stats{};
   const uint64_t stamp = ++c->wave_counter;
-  const uint32_t small_max = c->cfg.small_block_elems;
-
-  // pass 1: validation only, so that an error leaves no trace
+  c->sig.clear();
   for (int64_t i = 0; i < n; ++i) {
     Job* j = find_job(c, list[i].job);
     if (!j) return PS_ERR_BAD_JOB;
@@ -174,9 +184,21 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
     if (b.wave_stamp == stamp) return PS_ERR_DUP_BLOCK;
     b.wave_stamp = stamp;
     if (need_pushes && b.mask != j->full_mask) return PS_ERR_NOT_READY;
+    c->sig.push_back(((uint64_t)(uint32_t)list[i].job << 32) | (uint32_t)list[i].block);
+    for (int32_t w = 0; w < j->W; ++w)
+      c->sig.push_back((b.mask >> w) & 1u ? (uint64_t)reinterpret_cast<uintptr_t>(b.grad[w]) : 0);
   }
+  return PS_OK;
+}
 
-  // pass 2: one record per listed block, in list order; small blocks go to bins
+// Lay out the tables of a validated list's wave in P.
+void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
+  P.recs.clear(); P.rec_of.clear(); P.large_order.clear(); P.tiles.clear(); P.chunks.clear();
+  P.small_entries.clear(); P.bins.clear(); P.large_recs.clear();
+  P.stats = ps_wave_stats{};
+  const uint32_t small_max = c->cfg.small_block_elems;
+
+  // one record per listed block, in list order; small blocks go to bins
   P.rec_of.resize((size_t)n);
   PsBin bin{0, 0, 0, 0};
   auto close_bin = [&]() {
@@ -220,7 +242,7 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
   }
   close_bin();
 
-  // pass 3: launch order of the large path.  Blocks are independent, so any
+  // launch order of the large path.  Blocks are independent, so any
   // order gives the same result; tiles of one worker count are made adjacent
   // (most workers first) and, inside a class, one job's blocks stay together,
   // which keeps the number of HBM streams touched at any moment small.
@@ -270,27 +292,31 @@ int32_t build_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pus
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
   P.stats.n_small_bins = (int64_t)P.bins.size();
   P.stats.n_launches = (int64_t)std::max<size_t>(P.chunks.size(), P.bins.empty() ? 0 : 1);
-  return PS_OK;
 }
 
-// Wait for the wave that last used the slot and add its event times to the sums.
+// Wait for the wave that last used the slot.
 int32_t slot_retire(ps_ctx* c, Slot& s) {
   if (!s.in_flight) return PS_OK;
   PS_HIP(c, hipEventSynchronize(s.done));
   s.in_flight = false;
-  if (s.timed) {
-    s.timed = false;
-    float ms[3] = {0, 0, 0};
-    for (int i = 0; i < 3; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], s.tev[i], s.tev[i + 1]));
-    float tot = 0;
-    PS_HIP(c, hipEventElapsedTime(&tot, s.tev[0], s.tev[3]));
-    c->timing.n_waves += 1;
-    c->timing.n_launches += s.launches;
-    c->timing.upload_ms += ms[0];
-    c->timing.agg_ms += ms[1];
-    c->timing.norms_ms += ms[2];
-    c->timing.total_ms += tot;
-  }
+  return PS_OK;
+}
+
+// Wait for a measured wave and add its event times to the sums.
+int32_t timing_harvest(ps_ctx* c, TimingSet& t) {
+  if (!t.pending) return PS_OK;
+  PS_HIP(c, hipEventSynchronize(t.ev[3]));
+  t.pending = false;
+  float ms[3] = {0, 0, 0};
+  for (int i = 0; i < 3; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], t.ev[i], t.ev[i + 1]));
+  float tot = 0;
+  PS_HIP(c, hipEventElapsedTime(&tot, t.ev[0], t.ev[3]));
+  c->timing.n_waves += 1;
+  c->timing.n_launches += t.launches;
+  c->timing.upload_ms += ms[0];
+  c->timing.agg_ms += ms[1];
+  c->timing.norms_ms += ms[2];
+  c->timing.total_ms += tot;
   return PS_OK;
 }
 
@@ -377,11 +403,13 @@ void ps_destroy(ps_ctx* c) {
   for (Slot& s : c->slots) {
     if (s.in_flight) (void)hipEventSynchronize(s.done);
     if (s.done) (void)hipEventDestroy(s.done);
-    for (hipEvent_t e : s.tev)
-      if (e) (void)hipEventDestroy(e);
+
     if (s.host) (void)hipHostFree(s.host);
     if (s.dev) (void)hipFree(s.dev);
   }
+  for (TimingSet& t : c->tsets)
+    for (hipEvent_t e : t.ev)
+      if (e) (void)hipEventDestroy(e);
   for (Job& j : c->jobs) {
     if (j.stat && c->cfg.arena_dev) (void)hipHostFree(j.stat);
     else delete[] j.stat;
@@ -592,8 +620,9 @@ int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_r
 int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_stats* out) {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
-  const int32_t st = build_plan(c, list, n, /*need_pushes=*/true);
+  const int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
   if (st != PS_OK) return st;
+  layout_plan(c, list, n, c->plan);
   *out = c->plan.stats;
   return PS_OK;
 }
@@ -601,60 +630,93 @@ int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_sta
 int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
-  int32_t st = build_plan(c, list, n, /*need_pushes=*/true);
+  int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
   if (st != PS_OK) return st;
   if (n == 0) return PS_OK;
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
-  Plan& P = c->plan;
-
-  size_t cur = 0;
-  const size_t o_recs = place<unsigned char>(&cur, P.recs.size());
-  const size_t o_tiles = place<PsTile>(&cur, P.tiles.size());
-  const size_t o_small = place<PsSmallEntry>(&cur, P.small_entries.size());
-  const size_t o_bins = place<PsBin>(&cur, P.bins.size());
-  const size_t o_large = place<uint32_t>(&cur, P.large_recs.size());
-  const size_t upload = cur;
-  const size_t o_part = place<double>(&cur, P.tiles.size());
-  const size_t dev_total = cur;
-
-  Slot& s = c->slots[c->next_slot];
-  c->next_slot = (c->next_slot + 1) % kSlots;
-  st = slot_reserve(c, s, upload, dev_total);
-  if (st != PS_OK) return st;
-  auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(s.host + at, src, bytes); };
-  put(o_recs, P.recs.data(), P.recs.size());
-  put(o_tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
-  put(o_small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
-  put(o_bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
-  put(o_large, P.large_recs.data(), P.large_recs.size() * sizeof(uint32_t));
-
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  PsWaveTables t{};
-  if (c->timing_on) {
-    for (int i = 0; i < 4; ++i)
-      if (!s.tev[i]) PS_HIP(c, hipEventCreate(&s.tev[i]));
-    PS_HIP(c, hipEventRecord(s.tev[0], hs));
-    for (int i = 0; i < 3; ++i) t.ev[i] = s.tev[i + 1];
+
+  // Steady-state training repeats the same wave with the same gradient buffers:
+  // if the previous wave's tables still describe this one, use them as they are.
+  Slot* sp = nullptr;
+  bool reuse = false;
+  if (c->last_slot >= 0) {
+    Slot& ls = c->slots[c->last_slot];
+    if (ls.valid && ls.plan.sig == c->sig) {
+      sp = &ls;
+      reuse = true;
+      // tables and tile partials are shared with the slot's previous wave
+      if (ls.in_flight && ls.stream != hs) PS_HIP(c, hipStreamWaitEvent(hs, ls.done, 0));
+    }
   }
-  PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
-  t.recs = reinterpret_cast<const unsigned char*>(s.dev + o_recs);
-  t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
-  t.n_tiles = (uint32_t)P.tiles.size();
-  t.chunks = P.chunks.data();
-  t.n_chunks = (uint32_t)P.chunks.size();
-  t.tile_part = reinterpret_cast<double*>(s.dev + o_part);
-  t.small_entries = reinterpret_cast<const PsSmallEntry*>(s.dev + o_small);
-  t.bins = reinterpret_cast<const PsBin*>(s.dev + o_bins);
-  t.n_bins = (uint32_t)P.bins.size();
-  t.large_recs = reinterpret_cast<const uint32_t*>(s.dev + o_large);
-  t.n_large_blocks = (uint32_t)P.large_recs.size();
-  t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
+  TimingSet* ts = nullptr;
+  if (c->timing_on) {
+    ts = &c->tsets[c->next_tset];
+    c->next_tset = (c->next_tset + 1) % kTimingSets;
+    st = timing_harvest(c, *ts);
+    if (st != PS_OK) return st;
+    for (hipEvent_t& e : ts->ev)
+      if (!e) PS_HIP(c, hipEventCreate(&e));
+    PS_HIP(c, hipEventRecord(ts->ev[0], hs));
+  }
+  if (!reuse) {
+    c->next_slot = (c->last_slot + 1) % kSlots;
+    sp = &c->slots[c->next_slot];
+    Slot& s = *sp;
+    s.valid = false;
+    Plan& P = s.plan;
+    layout_plan(c, list, n, P);
+    size_t cur = 0;
+    const size_t o_recs = place<unsigned char>(&cur, P.recs.size());
+    const size_t o_tiles = place<PsTile>(&cur, P.tiles.size());
+    const size_t o_small = place<PsSmallEntry>(&cur, P.small_entries.size());
+    const size_t o_bins = place<PsBin>(&cur, P.bins.size());
+    const size_t o_large = place<uint32_t>(&cur, P.large_recs.size());
+    const size_t upload = cur;
+    const size_t o_part = place<double>(&cur, P.tiles.size());
+    const size_t dev_total = cur;
+    st = slot_reserve(c, s, upload, dev_total);
+    if (st != PS_OK) return st;
+    auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(s.host + at, src, bytes); };
+    put(o_recs, P.recs.data(), P.recs.size());
+    put(o_tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
+    put(o_small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
+    put(o_bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
+    put(o_large, P.large_recs.data(), P.large_recs.size() * sizeof(uint32_t));
+    PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
+    PsWaveTables& t = s.tables;
+    t = PsWaveTables{};
+    t.recs = reinterpret_cast<const unsigned char*>(s.dev + o_recs);
+    t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
+    t.n_tiles = (uint32_t)P.tiles.size();
+    t.chunks = P.chunks.data();
+    t.n_chunks = (uint32_t)P.chunks.size();
+    t.tile_part = reinterpret_cast<double*>(s.dev + o_part);
+    t.small_entries = reinterpret_cast<const PsSmallEntry*>(s.dev + o_small);
+    t.bins = reinterpret_cast<const PsBin*>(s.dev + o_bins);
+    t.n_bins = (uint32_t)P.bins.size();
+    t.large_recs = reinterpret_cast<const uint32_t*>(s.dev + o_large);
+    t.n_large_blocks = (uint32_t)P.large_recs.size();
+    t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
+    P.sig = c->sig;
+  }
+  Slot& s = *sp;
+  PsWaveTables t = s.tables;
+  for (int i = 0; i < 3; ++i) t.ev[i] = ts ? ts->ev[i + 1] : nullptr;
   const int le = ps_launch_wave(t, stream);
-  if (le != 0) return hip_fail(c, (hipError_t)le, "launching the wave");
+  if (le != 0) {
+    s.valid = false;
+    return hip_fail(c, (hipError_t)le, "launching the wave");
+  }
   PS_HIP(c, hipEventRecord(s.done, hs));
   s.in_flight = true;
-  s.timed = c->timing_on;
-  s.launches = P.stats.n_launches;
+  s.stream = hs;
+  s.valid = true;
+  c->last_slot = (int)(sp - c->slots);
+  if (ts) {
+    ts->pending = true;
+    ts->launches = s.plan.stats.n_launches;
+  }
 
   // the wave is enqueued: consume the pushes
   for (int64_t i = 0; i < n; ++i) {
@@ -709,8 +771,8 @@ int32_t ps_timing_enable(ps_ctx* c, int32_t on) {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
-  for (Slot& s : c->slots) {
-    const int32_t st = slot_retire(c, s);
+  for (TimingSet& t : c->tsets) {
+    const int32_t st = timing_harvest(c, t);
     if (st != PS_OK) return st;
   }
   c->timing = ps_timing{};
@@ -721,8 +783,8 @@ int32_t ps_timing_enable(ps_ctx* c, int32_t on) {
 int32_t ps_timing_read(ps_ctx* c, ps_timing* out) {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
-  for (Slot& s : c->slots) {
-    const int32_t st = slot_retire(c, s);
+  for (TimingSet& t : c->tsets) {
+    const int32_t st = timing_harvest(c, t);
     if (st != PS_OK) return st;
   }
   *out = c->timing;

@@ -311,3 +311,31 @@ def test_full_size_packed_wave_sampled_blocks(orc):
         gap = slice(o + n, gpu.layer_flat[0][l + 1])
         assert not pf[gap].any() and not vf[gap].any()
     gpu.close()
+
+
+def test_repeated_and_changing_waves(orc):
+    """A repeated wave reuses the tables of the previous call; a wave whose
+    gradient buffers or block list changed must not.  Rounds alternate between
+    two sets of gradient buffers, then a round is cut in two, then the first set
+    returns; the oracle follows the same values."""
+    specs = [spec([30_000, 100, 4097, 5], 4), spec([64, 20_000], 2)]
+    gpu = GpuService(specs, 21, max_block_bytes=32 * 1024)
+    o = OracleService(orc, specs, 21, cap_elems=8 * 1024)
+    alt = [[torch.zeros_like(g) for g in gs] for gs in gpu.grads]
+    main = gpu.grads
+    wave = gpu.wave()
+    refs = wave.tolist()
+    plan = ["main", "main", "alt", "main", "split", "alt", "alt"]
+    for r, kind in enumerate(plan):
+        gpu.grads = alt if kind == "alt" else main
+        gpu.fill_grads(r)
+        gpu.push_all()
+        if kind == "split":
+            gpu.svc.aggregate(WaveList(refs[: len(refs) // 3]))
+            gpu.svc.aggregate(WaveList(refs[len(refs) // 3:]))
+        else:
+            gpu.svc.aggregate(wave)
+        o.step(r)
+        assert_state_equal(gpu, o, f"round {r} ({kind})")
+        assert_telemetry_close(gpu, o)
+    gpu.close()
