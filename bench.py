@@ -29,6 +29,11 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
+# HBM bytes per ps_agg_wave launch from rocprofv3 FETCH_SIZE + WRITE_SIZE counters
+# (scaled by a 1 GiB copy), for the default configuration of a workload.  Only
+# valid for the kernel as profiled: set an entry to None when the kernel changes.
+MEASURED_TRAFFIC_PER_LAUNCH = {"packed_wave": 33.967e9 / 125}
+
 
 def specs_for(name: str):
     import workloads as wl
@@ -183,7 +188,9 @@ def main() -> int:
         "step_frac_of_hbm_peak": stats.algorithmic_bytes * args.steps / dt / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm", "kernel": "ps_agg_wave", "achieved": achieved, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": (MEASURED_TRAFFIC_PER_LAUNCH.get(args.workload)
+                        if not (args.small_elems or args.launch_tiles or args.hold_permille) else None),
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_launch_ms,
             "launches": tm.n_launches, "launches_per_wave": stats.n_launches,
             "note": "avg_launch_ms = HIP-event time from the first to the last launch of a wave "
