@@ -14,3 +14,4 @@ from .binding import (  # noqa: F401
     WaveStats,
     load_library,
 )
+from .sched_binding import Scheduler  # noqa: F401,E402

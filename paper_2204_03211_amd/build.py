@@ -12,8 +12,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libps_agg.so")
-SOURCES = ["ps_service.cpp", "ps_kernels.hip"]
-HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(ROOT, "include", "ps.h")]
+SOURCES = ["ps_service.cpp", "ps_sched.cpp", "ps_kernels.hip"]
+HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(ROOT, "include", "ps.h"),
+           os.path.join(ROOT, "include", "ps_sched.h")]
 
 # -ffp-contract=off: the update's multiplies and adds must stay separate
 # roundings.  The packed-fp32 feature is switched off for device code.

