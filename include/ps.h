@@ -6,7 +6,7 @@
  * master copy of every registered job's parameters, collects the gradient
  * pushes of the job's W workers, aggregates them, updates the master copy with
  * the aggregated result, and answers pulls.  Aggregations are tensor-scale and
- * independent of each other (Section 2.3), so they are not grouped by job: one
+ * independent of each other (Section 2.2), so they are not grouped by job: one
  * call aggregates a list of blocks that may belong to many jobs, the way the
  * paper packs several jobs' aggregations onto one server (Section 3.1).  The
  * key of a piece of state is (job id, block id), as in Appendix A where the
@@ -63,7 +63,16 @@ enum {
   PS_ERR_NOMEM = -9,       /* arena exhausted, or a host/device allocation failed */
   PS_ERR_NO_DEVICE = -10,  /* the context was created without an arena (planning only) */
   PS_ERR_HIP = -11,        /* a HIP runtime call failed; see ps_last_error */
-  PS_ERR_CAPACITY = -12    /* an output array is too small; the needed count is reported */
+  PS_ERR_CAPACITY = -12,   /* an output array is too small; the needed count is reported */
+  PS_ERR_NOT_OWNER = -13,  /* the block's master copy is not (or no longer) held by this context */
+  PS_ERR_BUSY = -14        /* the block has pushes pending: it cannot start to migrate now */
+};
+
+/* Where a block's master copy is, as seen by one context. */
+enum {
+  PS_OWNER_HERE = 0,       /* this context holds it and aggregates it */
+  PS_OWNER_LEAVING = 1,    /* migration announced: still readable here, no pushes, no updates */
+  PS_OWNER_ELSEWHERE = 2   /* another context holds it */
 };
 
 enum {
@@ -112,6 +121,8 @@ typedef struct ps_block_info {
   int64_t round;          /* aggregations applied to this block so far */
   uint32_t push_mask;     /* bit w set = worker w has pushed for the current round */
   uint32_t small_path;    /* 1 if the block takes the small-block path */
+  uint32_t owner;         /* PS_OWNER_* */
+  uint32_t reserved_;
 } ps_block_info;
 
 typedef struct ps_block_stats {
@@ -168,6 +179,14 @@ int32_t ps_register_job(ps_ctx* ctx, const int64_t* layer_numel, int32_t n_layer
                         float lr, float momentum, float wd, const float* const* init_params,
                         void* stream, ps_job_t* out_job, int32_t* out_n_blocks);
 
+/* Register a job whose master copies live in another context for now: same
+ * layout and arena use as ps_register_job, but every block starts as
+ * PS_OWNER_ELSEWHERE and can only be filled by ps_migrate_copy.  This is the
+ * receiving side of the paper's tensor migration (Section 3.2, Appendix B). */
+int32_t ps_register_shadow_job(ps_ctx* ctx, const int64_t* layer_numel, int32_t n_layers, int32_t W,
+                               float lr, float momentum, float wd, void* stream, ps_job_t* out_job,
+                               int32_t* out_n_blocks);
+
 /* Forget a job.  Its arena space is reused only if it was the most recently
  * registered live job (the arena is a stack).  Pending pushes are dropped. */
 int32_t ps_unregister_job(ps_ctx* ctx, ps_job_t job);
@@ -206,6 +225,16 @@ int32_t ps_push_flat(ps_ctx* ctx, ps_job_t job, int32_t worker, const float* gra
 int32_t ps_pack_wave(ps_ctx* ctx, const ps_job_t* jobs, int32_t n_jobs, ps_block_ref* out,
                      int64_t cap, int64_t* out_n);
 
+/* Split a block list by readiness (late requests, Section 3.3.1 "Handling
+ * Outliers"): blocks that have all W pushes go to out_ready, the others to
+ * out_late, both in list order and each with room for n entries.  The caller
+ * aggregates out_ready now and decides with ps_sched_admit_late whether a late
+ * block may still join this cycle or waits for the next.  Validates ids,
+ * duplicates and ownership like ps_aggregate; changes no state. */
+int32_t ps_split_ready(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n,
+                       ps_block_ref* out_ready, int64_t* out_n_ready, ps_block_ref* out_late,
+                       int64_t* out_n_late);
+
 /* Validate a block list exactly as ps_aggregate would, and report how it would
  * be laid out on the GPU.  Changes no state, touches no device. */
 int32_t ps_plan_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, ps_wave_stats* out);
@@ -239,6 +268,32 @@ int32_t ps_pull_flat(ps_ctx* ctx, ps_job_t job, const float** out_param_dev,
  * into host-visible memory at the end of the wave: the caller must have
  * synchronised the wave's stream before reading. */
 int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* out);
+
+/* --- migration of a block's master copy between contexts ------------------- */
+/* The paper moves a tensor between Aggregators inside the window in which its
+ * master copy is idle -- after the last pull of an iteration and before the next
+ * update -- and keeps two rules: the old owner stops serving it once the move is
+ * announced, and the new owner never updates it before the copy is complete
+ * (Section 3.2 "Tensor Migration"; Appendix B).  Here an Aggregator is a
+ * context; both contexts hold the job (ps_register_job in one,
+ * ps_register_shadow_job in the other, same layers and W).
+ *
+ * ps_migrate_begin   announce (the paper's MIGRATE_INIT): the block must have no
+ *                    pending pushes (PS_ERR_BUSY otherwise).  It becomes
+ *                    PS_OWNER_LEAVING: pulls still work, pushes and aggregation
+ *                    return PS_ERR_NOT_OWNER.
+ * ps_migrate_cancel  undo an announcement.
+ * ps_migrate_copy    the paper's TENSOR_COPY: enqueue on stream the copy of the
+ *                    parameter and momentum shards and of the round counter from
+ *                    src to dst, ordered after src's updates in flight.  dst owns
+ *                    the block from this call on and may take pushes at once; its
+ *                    first ps_aggregate naming the block is ordered after the
+ *                    copy on whatever stream it runs (TENSOR_COPY_DONE).  src
+ *                    becomes PS_OWNER_ELSEWHERE. */
+int32_t ps_migrate_begin(ps_ctx* ctx, ps_job_t job, int32_t block);
+int32_t ps_migrate_cancel(ps_ctx* ctx, ps_job_t job, int32_t block);
+int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* dst, ps_job_t dst_job,
+                        void* stream);
 
 /* --- measurement ------------------------------------------------------------ */
 

@@ -7,7 +7,7 @@
 //
 // What is computed (paper, Section 2 "Background and Motivation": the server
 // holds the master copy of the parameters and updates it with the aggregated
-// result of the workers' pushes; Section 2.3 "Tensor-Based Model Structure":
+// result of the workers' pushes; Section 2.2 "Tensor-Based Model Structure":
 // tensors are aggregated independently of each other; Section 2.1: a tensor's
 // aggregation can start only when its backward pass is done, so gradients
 // arrive last layer first).  The paper leaves the optimizer, the precision and

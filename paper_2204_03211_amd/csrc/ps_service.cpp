@@ -34,6 +34,9 @@ struct Block {
   int64_t round = 0;
   uint32_t mask = 0;
   uint64_t wave_stamp = 0;  // id of the last list that named this block (duplicate check)
+  uint8_t owner = PS_OWNER_HERE;   // PS_OWNER_*
+  bool ready_pending = false;      // shard content arrives by a copy: wait for `ready` first
+  hipEvent_t ready = nullptr;
   const float* grad[PS_MAX_W];
 };
 
@@ -111,6 +114,7 @@ struct ps_ctx {
   bool timing_on = false;
   ps_timing timing{};
   double clock_hz = 1.0e8;      // rate of the device's wall clock
+  int64_t n_ready_pending = 0;  // blocks whose migrated content has not been waited for yet
   uint32_t resident_tiles[PS_MAX_W + 1] = {};  // per W: workgroups the chip holds at once (0 = unknown)
 };
 
@@ -183,6 +187,7 @@ int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_
     Block& b = j->blocks[list[i].block];
     if (b.wave_stamp == stamp) return PS_ERR_DUP_BLOCK;
     b.wave_stamp = stamp;
+    if (b.owner != PS_OWNER_HERE) return PS_ERR_NOT_OWNER;
     if (need_pushes && b.mask != j->full_mask) return PS_ERR_NOT_READY;
     c->sig.push_back(((uint64_t)(uint32_t)list[i].job << 32) | (uint32_t)list[i].block);
     for (int32_t w = 0; w < j->W; ++w)
@@ -371,6 +376,8 @@ const char* ps_strerror(int32_t s) {
     case PS_ERR_NO_DEVICE: return "planning context: no device arena";
     case PS_ERR_HIP: return "HIP runtime call failed";
     case PS_ERR_CAPACITY: return "output array too small";
+    case PS_ERR_NOT_OWNER: return "block's master copy is not held by this context";
+    case PS_ERR_BUSY: return "block has pushes pending";
     default: return "unknown status";
   }
 }
@@ -431,9 +438,9 @@ int32_t ps_job_arena_bytes(const ps_config* cfg, const int64_t* layer_numel, int
   return PS_OK;
 }
 
-int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
-                        float momentum, float wd, const float* const* init_params, void* stream,
-                        ps_job_t* out_job, int32_t* out_n_blocks) {
+static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
+                            float momentum, float wd, const float* const* init_params, void* stream,
+                            ps_job_t* out_job, int32_t* out_n_blocks, bool shadow) {
   if (!c || !out_job) return PS_ERR_ARG;
   if (W < 1 || W > PS_MAX_W) return PS_ERR_ARG;
   if (!std::isfinite(lr) || !std::isfinite(momentum) || !std::isfinite(wd)) return PS_ERR_ARG;
@@ -490,6 +497,8 @@ int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers,
   j.stat_round = new (std::nothrow) int64_t[nb];
   if (!j.stat_round) return PS_ERR_NOMEM;
   for (size_t b = 0; b < nb; ++b) { j.stat[b] = 0.0; j.stat_round[b] = 0; }
+  if (shadow)
+    for (Block& b : j.blocks) b.owner = PS_OWNER_ELSEWHERE;
   j.live = true;
   c->arena_top = round_up(j.arena_off + j.arena_bytes, PS_ALIGN_BYTES);
   c->jobs.push_back(std::move(j));
@@ -498,12 +507,30 @@ int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers,
   return PS_OK;
 }
 
+int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
+                        float momentum, float wd, const float* const* init_params, void* stream,
+                        ps_job_t* out_job, int32_t* out_n_blocks) {
+  return register_job(c, layer_numel, n_layers, W, lr, momentum, wd, init_params, stream, out_job,
+                      out_n_blocks, /*shadow=*/false);
+}
+
+int32_t ps_register_shadow_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W,
+                               float lr, float momentum, float wd, void* stream, ps_job_t* out_job,
+                               int32_t* out_n_blocks) {
+  return register_job(c, layer_numel, n_layers, W, lr, momentum, wd, nullptr, stream, out_job,
+                      out_n_blocks, /*shadow=*/true);
+}
+
 int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
   if (!j) return PS_ERR_BAD_JOB;
   j->live = false;
+  for (Block& b : j->blocks) {
+    if (b.ready_pending) c->n_ready_pending -= 1;
+    if (b.ready) (void)hipEventDestroy(b.ready);
+  }
   if (j->stat && c->cfg.arena_dev) (void)hipHostFree(j->stat);
   else delete[] j->stat;
   delete[] j->stat_round;
@@ -546,6 +573,8 @@ int32_t ps_job_block_info(ps_ctx* c, ps_job_t job, int32_t block, ps_block_info*
   out->round = b.round;
   out->push_mask = b.mask;
   out->small_path = b.numel <= (int64_t)c->cfg.small_block_elems ? 1u : 0u;
+  out->owner = b.owner;
+  out->reserved_ = 0;
   return PS_OK;
 }
 
@@ -558,6 +587,7 @@ int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const fl
   if (worker < 0 || worker >= j->W) return PS_ERR_BAD_WORKER;
   if (reinterpret_cast<uintptr_t>(grad_dev) % PS_GRAD_ALIGN_BYTES) return PS_ERR_ALIGN;
   Block& b = j->blocks[block];
+  if (b.owner != PS_OWNER_HERE) return PS_ERR_NOT_OWNER;
   if ((b.mask >> worker) & 1u) return PS_ERR_DUP_PUSH;
   b.grad[worker] = grad_dev;
   b.mask |= 1u << worker;
@@ -573,8 +603,9 @@ int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_
   if (reinterpret_cast<uintptr_t>(grad_flat_dev) % PS_ALIGN_BYTES) return PS_ERR_ALIGN;
   const uint32_t bit = 1u << worker;
   for (const Block& b : j->blocks)
-    if (b.mask & bit) return PS_ERR_DUP_PUSH;
+    if (b.owner == PS_OWNER_HERE && (b.mask & bit)) return PS_ERR_DUP_PUSH;
   for (Block& b : j->blocks) {
+    if (b.owner != PS_OWNER_HERE) continue;  // pushed to whoever owns it
     b.grad[worker] = grad_flat_dev + b.flat_off;
     b.mask |= bit;
   }
@@ -586,13 +617,17 @@ int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_r
   if (!c || !out_n || n_jobs < 0 || (n_jobs > 0 && !jobs) || cap < 0 || (cap > 0 && !out))
     return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
+  // each job's arrival sequence, restricted to the blocks this context owns
+  std::vector<std::vector<int32_t>> seq((size_t)n_jobs);
   int64_t total = 0;
   for (int32_t a = 0; a < n_jobs; ++a) {
     Job* j = find_job(c, jobs[a]);
     if (!j) return PS_ERR_BAD_JOB;
     for (int32_t b = 0; b < a; ++b)
       if (jobs[b] == jobs[a]) return PS_ERR_DUP_BLOCK;
-    total += (int64_t)j->arrival.size();
+    for (int32_t b : j->arrival)
+      if (j->blocks[b].owner == PS_OWNER_HERE) seq[a].push_back(b);
+    total += (int64_t)seq[a].size();
   }
   *out_n = total;
   if (total > cap) return PS_ERR_CAPACITY;
@@ -602,7 +637,7 @@ int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_r
     int32_t best = -1;
     int64_t bk = 0, bn = 1;
     for (int32_t a = 0; a < n_jobs; ++a) {
-      const int64_t n = (int64_t)c->jobs[jobs[a]].arrival.size();
+      const int64_t n = (int64_t)seq[a].size();
       const int64_t k = head[a];
       if (k >= n) continue;
       if (best < 0 || (unsigned __int128)(2 * k + 1) * (uint64_t)bn <
@@ -611,9 +646,89 @@ int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_r
       }
     }
     out[t].job = jobs[best];
-    out[t].block = c->jobs[jobs[best]].arrival[bk];
+    out[t].block = seq[best][bk];
     head[best] = bk + 1;
   }
+  return PS_OK;
+}
+
+int32_t ps_split_ready(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_block_ref* out_ready,
+                       int64_t* out_n_ready, ps_block_ref* out_late, int64_t* out_n_late) {
+  if (!c || !out_n_ready || !out_n_late) return PS_ERR_ARG;
+  if (n > 0 && (!out_ready || !out_late)) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  const int32_t st = validate_list(c, list, n, /*need_pushes=*/false);
+  if (st != PS_OK) return st;
+  int64_t nr = 0, nl = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    const Job& j = c->jobs[list[i].job];
+    if (j.blocks[list[i].block].mask == j.full_mask) out_ready[nr++] = list[i];
+    else out_late[nl++] = list[i];
+  }
+  *out_n_ready = nr;
+  *out_n_late = nl;
+  return PS_OK;
+}
+
+int32_t ps_migrate_begin(ps_ctx* c, ps_job_t job, int32_t block) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  Block& b = j->blocks[block];
+  if (b.owner != PS_OWNER_HERE) return PS_ERR_NOT_OWNER;
+  if (b.mask != 0) return PS_ERR_BUSY;  // pushes of the coming round are already in
+  b.owner = PS_OWNER_LEAVING;
+  return PS_OK;
+}
+
+int32_t ps_migrate_cancel(ps_ctx* c, ps_job_t job, int32_t block) {
+  if (!c) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  Block& b = j->blocks[block];
+  if (b.owner != PS_OWNER_LEAVING) return PS_ERR_NOT_OWNER;
+  b.owner = PS_OWNER_HERE;
+  return PS_OK;
+}
+
+int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* dst, ps_job_t dst_job,
+                        void* stream) {
+  if (!src || !dst || src == dst) return PS_ERR_ARG;
+  // both contexts change: take their locks in address order
+  std::mutex& m1 = src < dst ? src->mu : dst->mu;
+  std::mutex& m2 = src < dst ? dst->mu : src->mu;
+  std::lock_guard<std::mutex> g1(m1);
+  std::lock_guard<std::mutex> g2(m2);
+  Job* js = find_job(src, src_job);
+  Job* jd = find_job(dst, dst_job);
+  if (!js || !jd) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= js->blocks.size() || (size_t)block >= jd->blocks.size())
+    return PS_ERR_BAD_BLOCK;
+  Block& bs = js->blocks[block];
+  Block& bd = jd->blocks[block];
+  if (bs.owner != PS_OWNER_LEAVING || bd.owner != PS_OWNER_ELSEWHERE) return PS_ERR_NOT_OWNER;
+  if (bs.numel != bd.numel || js->W != jd->W) return PS_ERR_ARG;
+  if (!js->p || !jd->p) return PS_ERR_NO_DEVICE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  // the copy must see the source's last update of the shard, whatever stream ran it
+  for (Slot& s : src->slots)
+    if (s.in_flight && s.stream != hs) PS_HIP(src, hipStreamWaitEvent(hs, s.done, 0));
+  const size_t bytes = (size_t)bs.numel * 4;
+  PS_HIP(dst, hipMemcpyAsync(jd->p + bd.flat_off, js->p + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
+  PS_HIP(dst, hipMemcpyAsync(jd->v + bd.flat_off, js->v + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
+  if (!bd.ready) PS_HIP(dst, hipEventCreateWithFlags(&bd.ready, hipEventDisableTiming));
+  PS_HIP(dst, hipEventRecord(bd.ready, hs));
+  // the new owner may take pushes at once; its first update waits for the copy
+  if (!bd.ready_pending) dst->n_ready_pending += 1;
+  bd.ready_pending = true;
+  bd.owner = PS_OWNER_HERE;
+  bd.round = bs.round;
+  bd.mask = 0;
+  bs.owner = PS_OWNER_ELSEWHERE;
   return PS_OK;
 }
 
@@ -635,6 +750,18 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   if (n == 0) return PS_OK;
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
   hipStream_t hs = static_cast<hipStream_t>(stream);
+
+  // A shard that arrived by migration must not be updated before its copy is
+  // complete (the new owner's consistency rule): order this stream after it.
+  if (c->n_ready_pending > 0) {
+    for (int64_t i = 0; i < n; ++i) {
+      Block& b = c->jobs[list[i].job].blocks[list[i].block];
+      if (!b.ready_pending) continue;
+      PS_HIP(c, hipStreamWaitEvent(hs, b.ready, 0));
+      b.ready_pending = false;
+      c->n_ready_pending -= 1;
+    }
+  }
 
   // Steady-state training repeats the same wave with the same gradient buffers:
   // if the previous wave's tables still describe this one, use them as they are.

@@ -5,7 +5,7 @@ pinned by what mathematics fixes: closed forms of the momentum recurrence in
 exact rationals on dyadic inputs (bit-exact), hand-derived IEEE-754 rounding
 cases that separate the prescribed evaluation order from its plausible
 variants, the library routine torch.optim.SGD as the W=1 special case, a
-binary64 error bound, and the independence of blocks (paper, Section 2.3,
+binary64 error bound, and the independence of blocks (paper, Section 2.2,
 "Tensor-Based Model Structure").
 """
 from fractions import Fraction as Fr
