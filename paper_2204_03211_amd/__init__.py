@@ -3,6 +3,9 @@ workers' gradient pushes + momentum-SGD update of the master copy) as HIP
 kernels behind a C ABI.  See include/ps.h for the boundary."""
 from .binding import (  # noqa: F401
     FLAG_FP_CONTRACT,
+    OWNER_ELSEWHERE,
+    OWNER_HERE,
+    OWNER_LEAVING,
     PS_MAX_W,
     BlockInfo,
     BlockRef,

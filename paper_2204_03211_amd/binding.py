@@ -21,7 +21,9 @@ ERRORS = {
     -1: "PS_ERR_ARG", -2: "PS_ERR_BAD_JOB", -3: "PS_ERR_BAD_BLOCK", -4: "PS_ERR_BAD_WORKER",
     -5: "PS_ERR_DUP_PUSH", -6: "PS_ERR_NOT_READY", -7: "PS_ERR_DUP_BLOCK", -8: "PS_ERR_ALIGN",
     -9: "PS_ERR_NOMEM", -10: "PS_ERR_NO_DEVICE", -11: "PS_ERR_HIP", -12: "PS_ERR_CAPACITY",
+    -13: "PS_ERR_NOT_OWNER", -14: "PS_ERR_BUSY",
 }
+OWNER_HERE, OWNER_LEAVING, OWNER_ELSEWHERE = 0, 1, 2
 
 
 class PsError(RuntimeError):
@@ -44,7 +46,8 @@ class BlockRef(C.Structure):
 class BlockInfo(C.Structure):
     _fields_ = [("layer", C.c_int32), ("W", C.c_int32), ("layer_offset", C.c_int64),
                 ("numel", C.c_int64), ("flat_offset", C.c_int64), ("round", C.c_int64),
-                ("push_mask", C.c_uint32), ("small_path", C.c_uint32)]
+                ("push_mask", C.c_uint32), ("small_path", C.c_uint32), ("owner", C.c_uint32),
+                ("reserved_", C.c_uint32)]
 
 
 class BlockStats(C.Structure):
@@ -64,7 +67,8 @@ class Timing(C.Structure):
 
 
 EXPORTS = [
-    "ps_create", "ps_destroy", "ps_job_arena_bytes", "ps_register_job", "ps_unregister_job",
+    "ps_create", "ps_destroy", "ps_job_arena_bytes", "ps_register_job", "ps_register_shadow_job",
+    "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
     "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat",
     "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
@@ -90,6 +94,12 @@ def load_library() -> C.CDLL:
     L.ps_job_arena_bytes.argtypes = [P(Config), P(i64), i32, P(u64)]
     L.ps_register_job.argtypes = [vp, P(i64), i32, i32, C.c_float, C.c_float, C.c_float,
                                   P(vp), vp, P(i32), P(i32)]
+    L.ps_register_shadow_job.argtypes = [vp, P(i64), i32, i32, C.c_float, C.c_float, C.c_float,
+                                         vp, P(i32), P(i32)]
+    L.ps_split_ready.argtypes = [vp, P(BlockRef), i64, P(BlockRef), P(i64), P(BlockRef), P(i64)]
+    L.ps_migrate_begin.argtypes = [vp, i32, i32]
+    L.ps_migrate_cancel.argtypes = [vp, i32, i32]
+    L.ps_migrate_copy.argtypes = [vp, i32, i32, vp, i32, vp]
     L.ps_unregister_job.argtypes = [vp, i32]
     L.ps_job_n_blocks.argtypes = [vp, i32]
     L.ps_job_flat_numel.argtypes = [vp, i32]
@@ -210,6 +220,34 @@ class ParameterService:
         self._check(self.L.ps_register_job(self.ctx, arr, n, W, lr, momentum, wd, ptrs, sp,
                                            C.byref(job), C.byref(nb)))
         return job.value, nb.value
+
+    def register_shadow_job(self, layer_numel: Sequence[int], W: int, lr: float, momentum: float,
+                            wd: float, stream: Optional[torch.cuda.Stream] = None) -> Tuple[int, int]:
+        n = len(layer_numel)
+        arr = (C.c_int64 * max(n, 1))(*layer_numel)
+        job, nb = C.c_int32(), C.c_int32()
+        sp = _stream_ptr(stream) if self.arena is not None else None
+        self._check(self.L.ps_register_shadow_job(self.ctx, arr, n, W, lr, momentum, wd, sp,
+                                                  C.byref(job), C.byref(nb)))
+        return job.value, nb.value
+
+    def split_ready(self, wave: WaveList) -> Tuple[WaveList, WaveList]:
+        ready = (BlockRef * max(wave.n, 1))()
+        late = (BlockRef * max(wave.n, 1))()
+        nr, nl = C.c_int64(), C.c_int64()
+        self._check(self.L.ps_split_ready(self.ctx, wave.arr, wave.n, ready, C.byref(nr), late, C.byref(nl)))
+        return WaveList(_arr=ready, _n=nr.value), WaveList(_arr=late, _n=nl.value)
+
+    def migrate_begin(self, job: int, block: int) -> None:
+        self._check(self.L.ps_migrate_begin(self.ctx, job, block))
+
+    def migrate_cancel(self, job: int, block: int) -> None:
+        self._check(self.L.ps_migrate_cancel(self.ctx, job, block))
+
+    def migrate_copy(self, job: int, block: int, dst: "ParameterService", dst_job: int,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+        sp = _stream_ptr(stream) if self.arena is not None else None
+        self._check(self.L.ps_migrate_copy(self.ctx, job, block, dst.ctx, dst_job, sp))
 
     def unregister_job(self, job: int) -> None:
         self._check(self.L.ps_unregister_job(self.ctx, job))

@@ -18,7 +18,7 @@ def declared_functions(header="ps.h"):
 
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 25
     lib = ctypes.CDLL(build.LIB) if os.path.exists(build.LIB) else load_library()
     for n in names:
         assert getattr(lib, n) is not None, n

@@ -383,3 +383,77 @@ def test_cyclic_execution_plan_drives_the_waves(orc):
     assert_state_equal(gpu, o, "after three cycles")
     assert_telemetry_close(gpu, o)
     gpu.close()
+
+
+def test_migration_between_two_contexts_keeps_the_trajectory(orc):
+    """Tensor migration (Section 3.2; Appendix B): blocks move between two
+    contexts ("Aggregators") in the window after a round's update and before the
+    next round's pushes; the new owner's first update is ordered after the copy
+    even on another stream.  The training trajectory must be bit-identical to
+    the oracle's, which knows nothing of migration."""
+    from paper_2204_03211_amd import OWNER_ELSEWHERE, OWNER_HERE, ParameterService
+    s = spec([40_000, 100, 4097, 9000], 4)
+    seed = 77
+    cap_bytes = 16 * 1024
+    need = ParameterService.job_arena_bytes(s.layer_numel, cap_bytes) + 256
+    dev = torch.device("cuda:0")
+    arena_a = torch.empty(need, dtype=torch.uint8, device=dev)
+    arena_b = torch.empty(need, dtype=torch.uint8, device=dev)
+    A, B = ParameterService(arena_a, cap_bytes), ParameterService(arena_b, cap_bytes)
+    init = [layer_values(seed, "param", (0, l), n, s.param_std, dev) for l, n in enumerate(s.layer_numel)]
+    ja, nb = A.register_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd, init)
+    jb, nb2 = B.register_shadow_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd)
+    assert nb == nb2
+    infos = [A.job_block_info(ja, b) for b in range(nb)]
+    flat_n = A.job_flat_numel(ja)
+    grads = [torch.zeros(flat_n, dtype=torch.float32, device=dev) for _ in range(s.W)]
+    layer_flat = {i.layer: i.flat_offset for i in infos if i.layer_offset == 0}
+    o = OracleService(orc, [s], seed, cap_elems=cap_bytes // 4)
+    side = torch.cuda.Stream()
+    owner = {b: (A, ja) for b in range(nb)}
+    rng = np.random.default_rng(3)
+
+    def other(svc):
+        return (B, jb) if svc is A else (A, ja)
+
+    for r in range(6):
+        for w in range(s.W):
+            for l, n in enumerate(s.layer_numel):
+                wl.fill_normal_like(grads[w][layer_flat[l]:layer_flat[l] + n],
+                                    wl.stream_key(seed, "grad", 0, w, r, l), s.grad_std)
+        for b in range(nb):
+            svc, job = owner[b]
+            off = infos[b].flat_offset
+            for w in range(s.W):
+                svc.push(job, b, w, grads[w][off:off + infos[b].numel])
+        # the two Aggregators run their shares on different streams
+        torch.cuda.synchronize()
+        A.aggregate(A.pack_wave([ja]))
+        with torch.cuda.stream(side):
+            B.aggregate(B.pack_wave([jb]))
+        o.step(r)
+        torch.cuda.synchronize()
+        # idle window: move a few blocks to the other side, the copy on the side stream
+        for b in rng.choice(nb, size=max(1, nb // 3), replace=False):
+            b = int(b)
+            svc, job = owner[b]
+            dst, dst_job = other(svc)
+            svc.migrate_begin(job, b)
+            svc.migrate_copy(job, b, dst, dst_job, stream=side)
+            assert svc.job_block_info(job, b).owner == OWNER_ELSEWHERE
+            assert dst.job_block_info(dst_job, b).owner == OWNER_HERE
+            assert dst.job_block_info(dst_job, b).round == r + 1
+            owner[b] = (dst, dst_job)
+        # no synchronisation here on purpose: the next aggregate must wait by itself
+    torch.cuda.synchronize()
+    moved = sum(1 for b in range(nb) if owner[b][0] is B)
+    assert 0 < moved < nb
+    for b in range(nb):
+        svc, job = owner[b]
+        layer, off, n = o.jobs[0].blocks[b]
+        want_p = o.jobs[0].p[layer][off:off + n]
+        want_v = o.jobs[0].v[layer][off:off + n]
+        assert np.array_equal(bits(svc.pull(job, b).cpu().numpy()), bits(want_p)), b
+        assert np.array_equal(bits(svc.pull_momentum(job, b).cpu().numpy()), bits(want_v)), b
+        assert svc.job_block_info(job, b).round == 6
+    A.close(); B.close()

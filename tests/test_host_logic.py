@@ -179,3 +179,72 @@ def test_argument_errors_and_unregister():
         svc.unregister_job(a)
     assert svc.job_n_blocks(b) == 1
     assert load_library().ps_strerror(-6).decode().startswith("block has not")
+
+
+def test_split_ready_and_late_admission():
+    """Late requests (Section 3.3.1, "Handling Outliers"): the wave takes the
+    blocks whose pushes are complete; a late block joins the current cycle only
+    if the time left after the work still scheduled covers it."""
+    from paper_2204_03211_amd import Scheduler
+    svc = ParameterService(None)
+    job, nb = reg(svc, [5000, 10, 300], W=2)
+    wave = svc.pack_wave([job])
+    svc.push_flat(job, 0, FAKE)
+    svc.push(job, 0, 1, FAKE)
+    svc.push(job, 2, 1, FAKE)                     # block 1 still lacks worker 1
+    ready, late = svc.split_ready(wave)
+    assert ready.tolist() == [(job, 2), (job, 0)] and late.tolist() == [(job, 1)]
+    assert svc.plan_wave(ready).n_blocks == 2
+    with pytest.raises(PsError) as ei:
+        svc.plan_wave(wave)
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    # cycle 12 ms, 7 ms gone, 3 ms of scheduled work left: a 2 ms straggler fits, a 2.5 ms one waits
+    assert Scheduler.admit_late(12.0, 7.0, 3.0, 2.0)
+    assert not Scheduler.admit_late(12.0, 7.0, 3.0, 2.5)
+    svc.push(job, 1, 1, FAKE)
+    ready, late = svc.split_ready(wave)
+    assert len(ready) == 3 and len(late) == 0
+    for bad, name in [(wave.tolist() + [(job, 0)], "PS_ERR_DUP_BLOCK"), ([(job, 9)], "PS_ERR_BAD_BLOCK")]:
+        with pytest.raises(PsError) as ei:
+            svc.split_ready(WaveList(bad))
+        assert ei.value.name == name
+
+
+def test_ownership_states_on_the_host():
+    """Migration bookkeeping without a device: announce / cancel, what each state
+    refuses, and a shadow registration that owns nothing."""
+    from paper_2204_03211_amd import OWNER_ELSEWHERE, OWNER_HERE, OWNER_LEAVING
+    a, b = ParameterService(None), ParameterService(None)
+    ja, nb = reg(a, [5000, 10], W=2)
+    jb, nb2 = b.register_shadow_job([5000, 10], 2, 0.1, 0.9, 1e-4)
+    assert nb == nb2 == 2
+    assert [b.job_block_info(jb, k).owner for k in range(2)] == [OWNER_ELSEWHERE] * 2
+    assert b.pack_wave([jb]).tolist() == []                  # nothing to aggregate there
+    with pytest.raises(PsError) as ei:
+        b.push(jb, 0, 0, FAKE)
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+    a.push(ja, 0, 0, FAKE)
+    with pytest.raises(PsError) as ei:
+        a.migrate_begin(ja, 0)                               # a push of the coming round is in
+    assert ei.value.name == "PS_ERR_BUSY"
+    a.migrate_begin(ja, 1)
+    assert a.job_block_info(ja, 1).owner == OWNER_LEAVING
+    with pytest.raises(PsError) as ei:
+        a.push(ja, 1, 0, FAKE)
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+    assert a.pack_wave([ja]).tolist() == [(ja, 0)]
+    with pytest.raises(PsError) as ei:
+        a.plan_wave(WaveList([(ja, 1)]))
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+    with pytest.raises(PsError) as ei:
+        a.migrate_begin(ja, 1)
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+    a.push_flat(ja, 1, FAKE)                                  # skips the leaving block
+    assert a.job_block_info(ja, 1).push_mask == 0 and a.job_block_info(ja, 0).push_mask == 0b11
+    with pytest.raises(PsError) as ei:
+        a.migrate_copy(ja, 1, b, jb)                          # no device behind these contexts
+    assert ei.value.name == "PS_ERR_NO_DEVICE"
+    a.migrate_cancel(ja, 1)
+    assert a.job_block_info(ja, 1).owner == OWNER_HERE
+    with pytest.raises(PsError):
+        a.migrate_cancel(ja, 1)
