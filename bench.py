@@ -83,6 +83,45 @@ def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
     }
 
 
+def migration_bench(spec, reps: int):
+    """Move all blocks of one job from one context to another and back, reps
+    times; the time is what a job would wait if nothing hid it (GPU time of the
+    announce + copy calls, HIP events on the copy stream)."""
+    import torch
+    from paper_2204_03211_amd import ParameterService
+    dev = torch.device("cuda:0")
+    need = ParameterService.job_arena_bytes(spec.layer_numel) + 256
+    arenas = [torch.zeros(need, dtype=torch.uint8, device=dev) for _ in range(2)]
+    svcs = [ParameterService(a) for a in arenas]
+    ja, nb = svcs[0].register_job(spec.layer_numel, spec.W, spec.lr, spec.momentum, spec.wd)
+    jb, _ = svcs[1].register_shadow_job(spec.layer_numel, spec.W, spec.lr, spec.momentum, spec.wd)
+    jobs = [ja, jb]
+    torch.cuda.synchronize()
+    times, host = [], []
+    src = 0
+    for _ in range(max(reps, 2)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        a.record()
+        for blk in range(nb):
+            svcs[src].migrate_begin(jobs[src], blk)
+            svcs[src].migrate_copy(jobs[src], blk, svcs[1 - src], jobs[1 - src])
+        b.record()
+        host.append((time.perf_counter() - t0) * 1e3)
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b))
+        src = 1 - src
+    times, host = times[1:], host[1:]
+    n_bytes = 8 * spec.n_params
+    ms = sum(times) / len(times)
+    out = {"migration": True, "model": spec.model, "blocks": nb, "params": spec.n_params,
+           "bytes_moved": n_bytes, "gpu_ms": ms, "host_call_ms": sum(host) / len(host),
+           "GB_per_s": n_bytes / ms / 1e6}
+    for s in svcs:
+        s.close()
+    return out
+
+
 def _cpu_model() -> str:
     try:
         for line in open("/proc/cpuinfo"):
@@ -101,6 +140,8 @@ def main() -> int:
     ap.add_argument("--workload", default="packed_wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--migration", action="store_true",
+                    help="instead: time moving every block of --workload's first job to a second context")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
     ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
@@ -126,6 +167,9 @@ def main() -> int:
                           "launches": 5}))
         return 0
     specs, seed = specs_for(args.workload)
+    if args.migration:
+        print(json.dumps(migration_bench(specs[0], args.steps)))
+        return 0
     t_setup = time.perf_counter()
     gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
                      store_hold_permille=args.hold_permille)

@@ -85,6 +85,14 @@ int32_t ps_sched_estimate(ps_sched* s, int32_t aggregator, int32_t job, double* 
 int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int32_t cap,
                             int32_t* out_n);
 
+/* Scaling up on arrival (Section 3.3.2): the caller has measured that `job` runs
+ * slower than standalone.  Allocates one more Aggregator and assigns the whole
+ * job again (its tasks in id order, Pseudocode 1 each) with the new one among
+ * the destinations; Aggregators left empty are released.  Repeat while the
+ * measured loss stays above the limit.  Writes the new Aggregator's id (which
+ * is released again if no task landed there). */
+int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator);
+
 int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_stats* out);
 int32_t ps_sched_job_info(ps_sched* s, int32_t job, ps_sched_job_stats* out);
 int32_t ps_sched_task_info(ps_sched* s, int32_t task, int32_t* out_aggregator, int32_t* out_job,

@@ -214,6 +214,28 @@ class SchedulerOracle:
         a.tasks.clear()
         return True
 
+    # -- scaling on job arrival (Section 3.3.2) ---------------------------------
+    def scale_up_job(self, k: int) -> int:
+        """The monitored job k runs slower than standalone: allocate one more
+        Aggregator and assign the whole job again, task by task in task-id order,
+        with the new (empty) Aggregator among the destinations.  The caller
+        repeats this while the measured loss stays above LossLimit.  Returns the
+        new Aggregator's id; Aggregators that end up empty are released."""
+        mine = sorted((t, e) for t, (n, j, e) in self.where.items() if j == k)
+        for t, e in mine:
+            n = self.where[t][0]
+            self.aggs[n].tasks[k].remove((t, e))
+            if not self.aggs[n].tasks[k]:
+                del self.aggs[n].tasks[k]
+        fresh = self.allocate()
+        for t, e in mine:
+            n = self.choose(k, e)
+            self._place(n, k, e, task=t)
+        for n in sorted(self.aggs):
+            if self.aggs[n].empty():
+                del self.aggs[n]
+        return fresh
+
     # -- two-level placement (Section 3.3.3) ------------------------------------
     @staticmethod
     def best_fit_cluster(free: List[float], demand: float) -> Optional[int]:

@@ -211,6 +211,25 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
   return PS_OK;
 }
 
+int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator) {
+  if (!s) return PS_ERR_ARG;
+  if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
+  std::vector<int32_t> mine;
+  for (int32_t t = 0; t < (int32_t)s->tasks.size(); ++t)
+    if (s->tasks[t].live && s->tasks[t].job == job) mine.push_back(t);
+  for (int32_t t : mine) s->unplace(t);
+  const int32_t fresh = s->allocate();
+  for (int32_t t : mine) {
+    int32_t n = s->choose(job, s->tasks[t].e, -1);
+    if (n < 0) n = s->allocate();
+    s->place(n, t);
+  }
+  for (auto& a : s->aggs)
+    if (a.live && a.by_job.empty()) a.live = false;
+  if (out_new_aggregator) *out_new_aggregator = fresh;
+  return PS_OK;
+}
+
 int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_stats* out) {
   if (!s || !out) return PS_ERR_ARG;
   if (!s->agg_ok(aggregator)) return PS_ERR_BAD_BLOCK;

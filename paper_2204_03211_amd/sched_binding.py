@@ -25,7 +25,7 @@ class Wave(C.Structure):
 
 SCHED_EXPORTS = [
     "ps_sched_create", "ps_sched_destroy", "ps_sched_add_job", "ps_sched_assign", "ps_sched_estimate",
-    "ps_sched_remove_job", "ps_sched_aggregator_info", "ps_sched_job_info", "ps_sched_task_info",
+    "ps_sched_remove_job", "ps_sched_scale_up_job", "ps_sched_aggregator_info", "ps_sched_job_info", "ps_sched_task_info",
     "ps_sched_aggregators", "ps_sched_cycle_plan", "ps_sched_admit_late", "ps_sched_best_fit_cluster",
 ]
 
@@ -44,6 +44,7 @@ def _lib():
         L.ps_sched_assign.argtypes = [vp, i32, dbl, P(i32), P(i32)]
         L.ps_sched_estimate.argtypes = [vp, i32, i32, P(dbl), P(dbl)]
         L.ps_sched_remove_job.argtypes = [vp, i32, P(i32), i32, P(i32)]
+        L.ps_sched_scale_up_job.argtypes = [vp, i32, P(i32)]
         L.ps_sched_aggregator_info.argtypes = [vp, i32, P(AggStats)]
         L.ps_sched_job_info.argtypes = [vp, i32, P(JobStats)]
         L.ps_sched_task_info.argtypes = [vp, i32, P(i32), P(i32), P(dbl)]
@@ -101,6 +102,11 @@ class Scheduler:
         out = (C.c_int32 * cap)()
         self._check(self.L.ps_sched_remove_job(self.h, job, out, cap, C.byref(n)))
         return list(out[:n.value])
+
+    def scale_up_job(self, job: int) -> int:
+        n = C.c_int32()
+        self._check(self.L.ps_sched_scale_up_job(self.h, job, C.byref(n)))
+        return n.value
 
     def aggregator_info(self, aggregator: int) -> AggStats:
         out = AggStats()

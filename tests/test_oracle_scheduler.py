@@ -186,3 +186,38 @@ def test_best_fit_cluster():
     assert f([5.0, 2.0, 9.0], 4.0) == 0
     assert f([5.0, 2.0, 9.0], 9.5) is None
     assert f([3.0, 3.0], 3.0) == 0
+
+
+def test_scale_up_gives_a_slow_job_room():
+    """Section 3.3.2: if a new job runs slower than alone, one more Aggregator is
+    added and the whole job is assigned again."""
+    s = SchedulerOracle()
+    a, b = s.add_job(10.0), s.add_job(10.0)
+    for _ in range(3):
+        s.assign(a, 2.0)
+    for _ in range(2):
+        s.assign(b, 2.0)                       # 10 of 10 used on Aggregator 0: no slack at all
+    assert sorted(s.aggs) == [0] and s.free(0) == 0.0
+    fresh = s.scale_up_job(b)
+    assert fresh == 1
+    # b's tasks are re-assigned by best fit: 0 has 4 free, 1 has 10: the first goes to 0 (tightest
+    # that fits), the second too (2 free >= 2)
+    assert sorted(n for n, j, e in s.where.values() if j == b) == [0, 0]
+    assert sorted(s.aggs) == [0]               # the unused new Aggregator is handed back
+    # a job too big for the slack does move
+    c = s.add_job(10.0)
+    s2 = SchedulerOracle()
+    x, y = s2.add_job(10.0), s2.add_job(10.0)
+    s2._place(s2.allocate(), x, 5.0)
+    s2._place(0, y, 3.0)
+    s2._place(0, y, 2.0)
+    s2.scale_up_job(y)                          # y off: 0 has 5 free; 3.0 -> 0 (5>=3), 2.0 -> 0 (2>=2)
+    assert all(n == 0 for n, j, e in s2.where.values())
+    s3 = SchedulerOracle()
+    x, y = s3.add_job(10.0), s3.add_job(10.0)
+    s3._place(s3.allocate(), x, 8.0)
+    s3._place(0, y, 1.5)
+    s3._place(0, y, 1.5)                         # over-full on purpose (11 of 10)
+    s3.scale_up_job(y)                           # 0 has 2 free: first 1.5 fits there, second (0.5 free) -> 1
+    assert sorted(n for n, j, e in s3.where.values() if j == y) == [0, 1]
+    assert sorted(s3.aggs) == [0, 1]
