@@ -457,3 +457,83 @@ def test_migration_between_two_contexts_keeps_the_trajectory(orc):
         assert np.array_equal(bits(svc.pull_momentum(job, b).cpu().numpy()), bits(want_v)), b
         assert svc.job_block_info(job, b).round == 6
     A.close(); B.close()
+
+
+def test_big_blocks_and_wide_jobs(orc):
+    """A 16 MiB block cap (one 5 M-element block: offsets far beyond one launch),
+    W = 32 on a multi-tile layer, and W = 1."""
+    for layers, W, cap in [([5_000_003], 2, 32 << 20), ([300_000, 77], 32, 0), ([1_200_000, 5], 1, 0)]:
+        s = spec(layers, W)
+        gpu = GpuService([s], 11, max_block_bytes=cap)
+        o = OracleService(orc, [s], 11, cap_elems=(cap or (4 << 20)) // 4, gen_device="cuda:0")
+        for r in range(2):
+            gpu.fill_grads(r)
+            gpu.step()
+            o.step(r)
+        assert_state_equal(gpu, o, f"layers {layers} W {W}")
+        assert_telemetry_close(gpu, o)
+        gpu.close()
+
+
+@pytest.mark.parametrize("launch_tiles,hold", [(3, 0), (0, -1), (7, 2000), (100000, 500)])
+def test_launch_shape_never_changes_results(orc, launch_tiles, hold):
+    """Tiles per launch and the store hold are performance knobs only."""
+    specs = [spec([100_000, 64, 4099], 8), spec([9000, 50_000], 2), spec([33_333], 5)]
+    gpu = GpuService(specs, 5, launch_tiles=launch_tiles, store_hold_permille=hold)
+    o = OracleService(orc, specs, 5)
+    for r in range(2):
+        gpu.fill_grads(r)
+        gpu.step()
+        o.step(r)
+    assert_state_equal(gpu, o)
+    assert_telemetry_close(gpu, o)
+    gpu.close()
+
+
+def test_two_streams_and_arena_reuse(orc):
+    """Waves of different jobs enqueued on two streams at once, then a job is
+    unregistered and its arena space taken by a new one."""
+    specs = [spec([60_000, 10], 4), spec([80_000, 300], 2)]
+    gpu = GpuService(specs, 8)
+    o = OracleService(orc, specs, 8)
+    side = torch.cuda.Stream()
+    for r in range(3):
+        gpu.fill_grads(r)
+        gpu.push_all()
+        torch.cuda.synchronize()
+        gpu.svc.aggregate(gpu.svc.pack_wave([gpu.jobs[0]]))
+        with torch.cuda.stream(side):
+            gpu.svc.aggregate(gpu.svc.pack_wave([gpu.jobs[1]]))
+        o.step(r)
+        torch.cuda.synchronize()
+    assert_state_equal(gpu, o)
+    # the last registered job leaves; a new one of another shape takes its place
+    svc = gpu.svc
+    top_before = svc.job_block_info(gpu.jobs[1], 0).flat_offset
+    p_old, _ = svc.pull_flat(gpu.jobs[1])
+    addr = p_old.data_ptr()
+    svc.unregister_job(gpu.jobs[1])
+    s2 = spec([50_000, 8], 3)
+    init = [layer_values(9, "param", (0, l), n, s2.param_std, "cuda:0") for l, n in enumerate(s2.layer_numel)]
+    j2, nb2 = svc.register_job(s2.layer_numel, s2.W, s2.lr, s2.momentum, s2.wd, init)
+    p_new, v_new = svc.pull_flat(j2)
+    assert p_new.data_ptr() == addr and top_before == 0
+    torch.cuda.synchronize()
+    assert not v_new.any()                                   # momentum starts from zero again
+    o2 = orc.OracleJob(tuple(s2.layer_numel), s2.W, s2.lr, s2.momentum, s2.wd)
+    for l in range(2):
+        o2.p[l][:] = init[l].cpu().numpy()
+    fn = svc.job_flat_numel(j2)
+    g = [torch.zeros(fn, device="cuda:0") for _ in range(s2.W)]
+    infos = [svc.job_block_info(j2, b) for b in range(nb2)]
+    for w in range(s2.W):
+        wl.fill_normal_like(g[w], wl.stream_key(9, "g", w), 1e-2)
+        svc.push_flat(j2, w, g[w])
+    svc.aggregate(svc.pack_wave([j2]))
+    torch.cuda.synchronize()
+    for b, i in enumerate(infos):
+        o2.aggregate(b, [g[w][i.flat_offset:i.flat_offset + i.numel].cpu().numpy() for w in range(s2.W)])
+    for b, i in enumerate(infos):
+        layer, off, n = o2.blocks[b]
+        assert np.array_equal(bits(svc.pull(j2, b).cpu().numpy()), bits(o2.p[layer][off:off + n]))
+    gpu.close()
