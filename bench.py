@@ -132,44 +132,12 @@ def _cpu_model() -> str:
     return "unknown"
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="packed_wave")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true")
-    ap.add_argument("--migration", action="store_true",
-                    help="instead: time moving every block of --workload's first job to a second context")
-    ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
-    ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
-    ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
-              "and no multi-GPU path exists; run with --gpus 1.", file=sys.stderr)
-        return 2
-
+def measure(workload: str, args, keep: bool):
+    """Time args.steps steps of one workload; returns (json object, service, last wave)."""
     import torch
     from harness import GpuService
 
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
-    if args.copy_calibration:
-        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
-        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        for _ in range(5):
-            torch.mul(src, 1.0, out=dst)              # an elementwise kernel: 1 read, 1 write
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": True, "bytes_read": 4 * n, "bytes_written": 4 * n,
-                          "launches": 5}))
-        return 0
-    specs, seed = specs_for(args.workload)
-    if args.migration:
-        print(json.dumps(migration_bench(specs[0], args.steps)))
-        return 0
+    specs, seed = specs_for(workload)
     t_setup = time.perf_counter()
     gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
                      store_hold_permille=args.hold_permille)
@@ -223,7 +191,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
-            "workload": args.workload, "jobs": len(specs), "W": [s.W for s in specs],
+            "workload": workload, "jobs": len(specs), "W": [s.W for s in specs],
             "models": [s.model for s in specs], "blocks": stats.n_blocks, "params": n_params,
             "block_cap_bytes": 4 << 20, "seed": seed,
             "algorithmic_bytes_per_step": stats.algorithmic_bytes,
@@ -233,7 +201,7 @@ def main() -> int:
         "roofline": {
             "bound": "hbm", "kernel": "ps_agg_wave", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": (MEASURED_TRAFFIC_PER_LAUNCH.get(args.workload)
+            "traffic": (MEASURED_TRAFFIC_PER_LAUNCH.get(workload)
                         if not (args.small_elems or args.launch_tiles or args.hold_permille) else None),
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_launch_ms,
             "launches": tm.n_launches, "launches_per_wave": stats.n_launches,
@@ -249,6 +217,65 @@ def main() -> int:
                        "params": stats.small_params},
         "setup_seconds": t_setup,
     }
+    if not keep:
+        gpu.close()
+        del gpu
+        torch.cuda.empty_cache()
+        return out, None, None
+    return out, gpu, wave
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="packed_wave")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-configs", action="store_true",
+                    help="skip the short single-job runs appended to the packed-wave line")
+    ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--migration", action="store_true",
+                    help="instead: time moving every block of --workload's first job to a second context")
+    ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
+    ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
+    ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
+              "and no multi-GPU path exists; run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 floats = 1 GiB read + 1 GiB written
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)              # an elementwise kernel: 1 read, 1 write
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read": 4 * n, "bytes_written": 4 * n,
+                          "launches": 5}))
+        return 0
+    specs, seed = specs_for(args.workload)
+    if args.migration:
+        print(json.dumps(migration_bench(specs[0], args.steps)))
+        return 0
+    out, gpu, wave = measure(args.workload, args, keep=True)
+    if args.workload == "packed_wave" and not args.no_side_configs:
+        # the single-job configurations, same step, fewer words: context for the headline line
+        side = {}
+        for name in ("alexnet", "resnet50", "vgg16"):
+            o, _, _ = measure(name, args, keep=False)
+            side[name] = {"params": o["config"]["params"], "W": o["config"]["W"][0],
+                          "ms_per_step": o["ms_per_step"], "params_per_s": o["value"],
+                          "step_GB_per_s": o["step_GB_per_s"],
+                          "kernel_GB_per_s": o["roofline"]["achieved"],
+                          "kernel_frac_of_hbm_peak": o["roofline"]["frac"]}
+        out["single_job_configs"] = side
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(gpu, wave.tolist())
     gpu.close()

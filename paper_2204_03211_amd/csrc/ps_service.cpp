@@ -54,7 +54,7 @@ struct Job {
   float* p = nullptr;
   float* v = nullptr;
   double* stat = nullptr;        // host-visible, one double per block
-  int64_t* stat_round = nullptr; // host only
+  std::vector<int64_t> stat_round; // host only: round each telemetry value belongs to
 };
 
 // HIP events bracketing the phases of one measured wave.
@@ -290,8 +290,13 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   // when each launch's reads are expected to be over, in wall-clock ticks
   const int32_t pm = c->cfg.store_hold_permille;
   const double frac = pm < 0 ? 0.0 : (pm == 0 ? PS_DEFAULT_HOLD_PERMILLE : pm) / 1000.0;
-  for (PsChunk& ch : P.chunks)
-    ch.hold_ticks = (uint32_t)(frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz);
+  for (PsChunk& ch : P.chunks) {
+    // holding only pays when the whole launch is resident; a larger launch (a
+    // caller's launch_tiles) would make every later generation wait again
+    const uint32_t resident = c->resident_tiles[ch.W <= PS_MAX_W ? ch.W : 0];
+    const bool fits = resident == 0 || ch.end - ch.begin <= resident;
+    ch.hold_ticks = fits ? (uint32_t)(frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz) : 0u;
+  }
 
   P.stats.n_blocks = n;
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
@@ -420,7 +425,6 @@ void ps_destroy(ps_ctx* c) {
   for (Job& j : c->jobs) {
     if (j.stat && c->cfg.arena_dev) (void)hipHostFree(j.stat);
     else delete[] j.stat;
-    delete[] j.stat_round;
   }
   delete c;
 }
@@ -494,9 +498,8 @@ static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_lay
     j.stat = new (std::nothrow) double[nb];
     if (!j.stat) return PS_ERR_NOMEM;
   }
-  j.stat_round = new (std::nothrow) int64_t[nb];
-  if (!j.stat_round) return PS_ERR_NOMEM;
-  for (size_t b = 0; b < nb; ++b) { j.stat[b] = 0.0; j.stat_round[b] = 0; }
+  j.stat_round.assign(nb, 0);
+  for (size_t b = 0; b < nb; ++b) j.stat[b] = 0.0;
   if (shadow)
     for (Block& b : j.blocks) b.owner = PS_OWNER_ELSEWHERE;
   j.live = true;
@@ -533,8 +536,8 @@ int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) {
   }
   if (j->stat && c->cfg.arena_dev) (void)hipHostFree(j->stat);
   else delete[] j->stat;
-  delete[] j->stat_round;
-  j->stat = nullptr; j->stat_round = nullptr;
+  j->stat = nullptr;
+  j->stat_round.clear();
   j->blocks.clear(); j->blocks.shrink_to_fit();
   // pop the arena stack past every dead job on top
   uint64_t top = 0;
