@@ -95,8 +95,8 @@ typedef struct ps_config {
                                  PS_ERR_NO_DEVICE */
   uint64_t arena_bytes;
   uint32_t launch_tiles;      /* tiles (4096 values each) per kernel launch of the large-block
-                                 path; 0 = chosen by worker count (1024 or 1536), never more
-                                 than fit on the chip at once */
+                                 path; 0 = as many as the chip holds at once (1792 on MI355X);
+                                 a larger value switches the store hold off for that launch */
   int32_t store_hold_permille; /* a launch's workgroups keep their results in registers and
                                  store them only once this fraction (in 1/1000) of the
                                  launch's predicted read time has passed since they
