@@ -537,3 +537,29 @@ def test_two_streams_and_arena_reuse(orc):
         layer, off, n = o2.blocks[b]
         assert np.array_equal(bits(svc.pull(j2, b).cpu().numpy()), bits(o2.p[layer][off:off + n]))
     gpu.close()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_configurations(orc, seed):
+    """Random jobs: worker counts 1..32, layer sizes from 1 to a few hundred
+    thousand, random block caps, small-path thresholds and hyper-parameters."""
+    rng = np.random.default_rng(1000 + seed)
+    n_jobs = int(rng.integers(1, 5))
+    specs = []
+    for _ in range(n_jobs):
+        n_layers = int(rng.integers(1, 7))
+        layers = [int(rng.choice([1, 7, 64, 100, 1023, 4096, 4097, 20_000, 65_536, 250_001]))
+                  + int(rng.integers(0, 5)) for _ in range(n_layers)]
+        specs.append(spec(layers, int(rng.integers(1, 33)), lr=float(rng.choice([0.01, 0.1, 1.0])),
+                          mu=float(rng.choice([0.0, 0.5, 0.9, 0.99])), wd=float(rng.choice([0.0, 1e-4, 0.1]))))
+    cap = int(rng.choice([1024, 4096, 64 * 1024, 1 << 20, 4 << 20]))
+    small = int(rng.choice([0, 64, 1000, 4096]))
+    gpu = GpuService(specs, seed, max_block_bytes=cap, small_block_elems=small)
+    o = OracleService(orc, specs, seed, cap_elems=cap // 4, gen_device="cuda:0")
+    for r in range(2):
+        gpu.fill_grads(r)
+        gpu.step()
+        o.step(r)
+    assert_state_equal(gpu, o, f"seed {seed}")
+    assert_telemetry_close(gpu, o)
+    gpu.close()
