@@ -1,0 +1,117 @@
+// Host-only exercise of the service's planning paths and of the scheduler, built
+// with AddressSanitizer and UBSan by tests/test_native_sanitizers.py.  No device
+// is touched: contexts are planning contexts (no arena), and the two functions
+// that live in the kernel file are stubbed here.
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <algorithm>
+#include <random>
+#include <vector>
+
+#include "../../include/ps.h"
+#include "../../include/ps_sched.h"
+#include "../../paper_2204_03211_amd/csrc/ps_internal.h"
+
+int ps_launch_wave(const PsWaveTables&, void*) { return 0; }
+uint32_t ps_resident_workgroups(uint32_t) { return 1792; }
+
+#define CHECK(x) do { if (!(x)) { std::printf("CHECK failed: %s (line %d)\n", #x, __LINE__); std::exit(1); } } while (0)
+
+static void service_rounds(uint64_t seed) {
+  std::mt19937_64 rng(seed);
+  ps_config cfg{};
+  cfg.max_block_bytes = (uint64_t)(1 + rng() % 64) * 256;
+  cfg.small_block_elems = (uint32_t)(rng() % 4097);
+  ps_ctx* ctx = nullptr;
+  CHECK(ps_create(&cfg, &ctx) == PS_OK);
+  std::vector<ps_job_t> jobs;
+  std::vector<int32_t> Ws;
+  const int n_jobs = 1 + (int)(rng() % 5);
+  for (int j = 0; j < n_jobs; ++j) {
+    std::vector<int64_t> layers(1 + rng() % 6);
+    for (auto& n : layers) n = 1 + (int64_t)(rng() % 20000);
+    const int32_t W = 1 + (int32_t)(rng() % 32);
+    ps_job_t job = -1;
+    int32_t nb = 0;
+    CHECK(ps_register_job(ctx, layers.data(), (int32_t)layers.size(), W, 0.1f, 0.9f, 1e-4f, nullptr,
+                          nullptr, &job, &nb) == PS_OK);
+    CHECK(nb == ps_job_n_blocks(ctx, job));
+    jobs.push_back(job);
+    Ws.push_back(W);
+  }
+  int64_t need = 0;
+  CHECK(ps_pack_wave(ctx, jobs.data(), n_jobs, nullptr, 0, &need) == (need ? PS_ERR_CAPACITY : PS_OK));
+  std::vector<ps_block_ref> wave((size_t)need);
+  CHECK(ps_pack_wave(ctx, jobs.data(), n_jobs, wave.data(), need, &need) == PS_OK);
+  const float* fake = reinterpret_cast<const float*>(uintptr_t(1) << 20);
+  for (int j = 0; j < n_jobs; ++j)
+    for (int32_t w = 0; w < Ws[j]; ++w) {
+      if (rng() % 7 == 0 && w == Ws[j] - 1) continue;  // leave a job incomplete now and then
+      CHECK(ps_push_flat(ctx, jobs[j], w, fake) == PS_OK);
+    }
+  std::vector<ps_block_ref> ready((size_t)need), late((size_t)need);
+  int64_t nr = 0, nl = 0;
+  CHECK(ps_split_ready(ctx, wave.data(), need, ready.data(), &nr, late.data(), &nl) == PS_OK);
+  CHECK(nr + nl == need);
+  ps_wave_stats st{};
+  CHECK(ps_plan_wave(ctx, ready.data(), nr, &st) == PS_OK);
+  CHECK(st.n_blocks == nr);
+  if (nl) CHECK(ps_plan_wave(ctx, wave.data(), need, &st) == PS_ERR_NOT_READY);
+  CHECK(ps_aggregate(ctx, ready.data(), nr, nullptr) == (nr ? PS_ERR_NO_DEVICE : PS_OK));
+  // shuffled and truncated lists, duplicates, bad ids
+  for (int k = 0; k < 4 && nr > 1; ++k) {
+    std::vector<ps_block_ref> l(ready.begin(), ready.begin() + nr);
+    std::shuffle(l.begin(), l.end(), rng);
+    l.resize(1 + rng() % l.size());
+    CHECK(ps_plan_wave(ctx, l.data(), (int64_t)l.size(), &st) == PS_OK);
+    l.push_back(l[0]);
+    CHECK(ps_plan_wave(ctx, l.data(), (int64_t)l.size(), &st) == PS_ERR_DUP_BLOCK);
+    l.back().block = 1 << 30;
+    CHECK(ps_plan_wave(ctx, l.data(), (int64_t)l.size(), &st) == PS_ERR_BAD_BLOCK);
+  }
+  if (n_jobs > 1) CHECK(ps_unregister_job(ctx, jobs[0]) == PS_OK);
+  ps_destroy(ctx);
+}
+
+static void scheduler_rounds(uint64_t seed) {
+  std::mt19937_64 rng(seed);
+  ps_sched* s = nullptr;
+  CHECK(ps_sched_create(0.0, &s) == PS_OK);
+  std::vector<int32_t> live;
+  const double Ds[] = {3, 4, 5, 6, 7.5, 9, 10, 12, 24};
+  for (int step = 0; step < 300; ++step) {
+    const unsigned r = (unsigned)(rng() % 100);
+    if (r < 12 || live.empty()) {
+      int32_t j = -1;
+      CHECK(ps_sched_add_job(s, Ds[rng() % 9], &j) == PS_OK);
+      live.push_back(j);
+    } else if (r < 90) {
+      int32_t t = -1, n = -1;
+      CHECK(ps_sched_assign(s, live[rng() % live.size()], 0.05 + (double)(rng() % 40) / 64.0, &t, &n) == PS_OK);
+      ps_sched_agg_stats a{};
+      CHECK(ps_sched_aggregator_info(s, n, &a) == PS_OK);
+      std::vector<ps_sched_wave> waves(64);
+      std::vector<int32_t> js(512);
+      int32_t nw = 0, nj = 0;
+      const int32_t rc = ps_sched_cycle_plan(s, n, waves.data(), 64, &nw, js.data(), 512, &nj);
+      CHECK(rc == PS_OK || rc == PS_ERR_CAPACITY);
+    } else if (r < 94) {
+      int32_t fresh = -1;
+      CHECK(ps_sched_scale_up_job(s, live[rng() % live.size()], &fresh) == PS_OK);
+    } else {
+      const size_t i = rng() % live.size();
+      int32_t rel[64], nrel = 0;
+      CHECK(ps_sched_remove_job(s, live[i], rel, 64, &nrel) == PS_OK);
+      live.erase(live.begin() + (long)i);
+    }
+  }
+  ps_sched_destroy(s);
+}
+
+int main() {
+  for (uint64_t seed = 1; seed <= 40; ++seed) service_rounds(seed);
+  for (uint64_t seed = 1; seed <= 10; ++seed) scheduler_rounds(seed);
+  std::printf("host sanitize driver: ok\n");
+  return 0;
+}

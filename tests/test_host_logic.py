@@ -248,3 +248,29 @@ def test_ownership_states_on_the_host():
     assert a.job_block_info(ja, 1).owner == OWNER_HERE
     with pytest.raises(PsError):
         a.migrate_cancel(ja, 1)
+
+
+def test_pushes_from_many_threads():
+    """One context, one mutex: W worker threads push their gradients for every
+    block at the same time; every mask ends up complete and nothing is lost."""
+    import threading
+    svc = ParameterService(None, max_block_bytes=1024)
+    W = 16
+    job, nb = reg(svc, [40_000, 3_000, 17], W=W)
+    errors = []
+
+    def worker(w):
+        try:
+            for b in range(nb):
+                svc.push(job, b, w, FAKE + 256 * w)
+        except Exception as e:          # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(w,)) for w in range(W)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    assert all(svc.job_block_info(job, b).push_mask == (1 << W) - 1 for b in range(nb))
+    assert svc.plan_wave(svc.pack_wave([job])).n_blocks == nb
