@@ -563,3 +563,108 @@ def test_random_configurations(orc, seed):
     assert_state_equal(gpu, o, f"seed {seed}")
     assert_telemetry_close(gpu, o)
     gpu.close()
+
+
+def test_elastic_scenario_scheduler_migration_training(orc):
+    """The paper's loop end to end on one GPU: contexts stand for Aggregators,
+    the scheduler places every block (Pseudocode 1), an "agent table" routes the
+    pushes, a job exit drains the least-loaded Aggregator and the blocks that
+    changed Aggregator migrate in the idle window.  Every job's trajectory must
+    equal the oracle's, which sees none of this."""
+    from paper_2204_03211_amd import ParameterService, Scheduler
+    dev = torch.device("cuda:0")
+    seed, cap_bytes, n_ctx = 55, 32 * 1024, 3
+    specs = [spec([60_000, 300], 4), spec([45_000, 64, 5000], 2), spec([70_000], 8)]
+    arenas = [torch.empty(sum(ParameterService.job_arena_bytes(s.layer_numel, cap_bytes) + 256 for s in specs),
+                          dtype=torch.uint8, device=dev) for _ in range(n_ctx)]
+    ctxs = [ParameterService(a, cap_bytes) for a in arenas]
+    o = OracleService(orc, specs, seed, cap_elems=cap_bytes // 4)
+    sch = Scheduler()
+    # every job is known to every Aggregator; context 0 holds the initial (temporary) copies
+    jid = [[None] * len(specs) for _ in range(n_ctx)]
+    infos, grads, layer_flat = [], [], []
+    for ji, s in enumerate(specs):
+        init = [layer_values(seed, "param", (ji, l), n, s.param_std, dev) for l, n in enumerate(s.layer_numel)]
+        jid[0][ji], nb = ctxs[0].register_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd, init)
+        for c in range(1, n_ctx):
+            jid[c][ji], _ = ctxs[c].register_shadow_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd)
+        inf = [ctxs[0].job_block_info(jid[0][ji], b) for b in range(nb)]
+        infos.append(inf)
+        layer_flat.append({i.layer: i.flat_offset for i in inf if i.layer_offset == 0})
+        grads.append([torch.zeros(ctxs[0].job_flat_numel(jid[0][ji]), device=dev) for _ in range(s.W)])
+    torch.cuda.synchronize()
+    agent = {(ji, b): 0 for ji in range(len(specs)) for b in range(len(infos[ji]))}   # block -> Aggregator
+
+    def move(ji, b, dst):
+        src = agent[(ji, b)]
+        if src == dst:
+            return
+        ctxs[src].migrate_begin(jid[src][ji], b)
+        ctxs[src].migrate_copy(jid[src][ji], b, ctxs[dst], jid[dst][ji])
+        agent[(ji, b)] = dst
+
+    # placement: iteration 10 ms each; a block's execution time from its bytes, scaled so that
+    # the three jobs do not fit one Aggregator
+    sj = [sch.add_job(10.0) for _ in specs]
+    task_of = {}
+    for ji, s in enumerate(specs):
+        for b, i in enumerate(infos[ji]):
+            e = (4 * s.W + 16) * i.numel / 1.0e6 * 1.8           # "ms"
+            t, agg = sch.assign(sj[ji], e)
+            task_of[(ji, b)] = t
+    aggs = sch.aggregators()
+    assert len(aggs) >= 2 and max(aggs) < n_ctx
+    for (ji, b), t in task_of.items():
+        move(ji, b, sch.task_info(t)[0])
+    live = [0, 1, 2]
+    rounds = [0, 0, 0]
+
+    def train_round():
+        for ji in live:
+            s, r = specs[ji], rounds[ji]
+            for w in range(s.W):
+                for l, n in enumerate(s.layer_numel):
+                    off = layer_flat[ji][l]
+                    wl.fill_normal_like(grads[ji][w][off:off + n],
+                                        wl.stream_key(seed, "grad", ji, w, r, l), s.grad_std)
+            for b, i in enumerate(infos[ji]):
+                c = agent[(ji, b)]
+                for w in range(s.W):
+                    ctxs[c].push(jid[c][ji], b, w, grads[ji][w][i.flat_offset:i.flat_offset + i.numel])
+        for c in range(n_ctx):
+            wave = ctxs[c].pack_wave([jid[c][ji] for ji in live])
+            if len(wave):
+                ctxs[c].aggregate(wave)
+        for ji in live:
+            for b in o.jobs[ji].arrival():
+                o.jobs[ji].aggregate(b, o.block_grads(ji, b, rounds[ji]))
+            rounds[ji] += 1
+
+    for _ in range(2):
+        train_round()
+    # job 1 leaves: Aggregators may be released, tasks of the others may move
+    before = {k: sch.task_info(t)[0] for k, t in task_of.items() if k[0] != 1}
+    released = sch.remove_job(sj[1])
+    live.remove(1)
+    moved = 0
+    for k, was in before.items():
+        now = sch.task_info(task_of[k])[0]
+        if now != was:
+            moved += 1
+        move(k[0], k[1], now)
+    assert set(agent[k] for k in before) <= set(sch.aggregators())
+    assert released == [1] and moved > 0 and sch.aggregators() == [0]   # the tail of job 2 came home
+    for _ in range(2):
+        train_round()
+    torch.cuda.synchronize()
+    for ji in live:
+        for b in range(len(infos[ji])):
+            c = agent[(ji, b)]
+            layer, off, n = o.jobs[ji].blocks[b]
+            assert np.array_equal(bits(ctxs[c].pull(jid[c][ji], b).cpu().numpy()),
+                                  bits(o.jobs[ji].p[layer][off:off + n])), (ji, b)
+            assert np.array_equal(bits(ctxs[c].pull_momentum(jid[c][ji], b).cpu().numpy()),
+                                  bits(o.jobs[ji].v[layer][off:off + n])), (ji, b)
+            assert ctxs[c].job_block_info(jid[c][ji], b).round == 4
+    for c in ctxs:
+        c.close()
