@@ -253,14 +253,17 @@ int32_t ps_aggregate(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, voi
 
 /* Borrowed DEVICE pointers to the block's parameters / momentum.  They stay
  * valid until the job is unregistered; their contents are those of the last
- * aggregation enqueued for the block, in stream order. */
+ * aggregation enqueued for the block, in stream order.  A block that has
+ * migrated away (PS_OWNER_ELSEWHERE) is PS_ERR_NOT_OWNER: pull from its new
+ * owner; one that is only leaving (PS_OWNER_LEAVING) still answers. */
 int32_t ps_pull(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_param_dev,
                 int64_t* out_numel);
 int32_t ps_pull_momentum(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_mom_dev,
                          int64_t* out_numel);
 
 /* Base DEVICE pointers of the job's flat parameter and momentum arrays
- * (ps_job_flat_numel floats each; block b starts at flat_offset). */
+ * (ps_job_flat_numel floats each; block b starts at flat_offset).  Regions of
+ * blocks this context does not own hold stale or unset data. */
 int32_t ps_pull_flat(ps_ctx* ctx, ps_job_t job, const float** out_param_dev,
                      const float** out_mom_dev, int64_t* out_flat_numel);
 

@@ -865,6 +865,7 @@ int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_
   Job* j = find_job(c, job);
   if (!j) return PS_ERR_BAD_JOB;
   if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  if (j->blocks[block].owner == PS_OWNER_ELSEWHERE) return PS_ERR_NOT_OWNER;  // ask the new owner
   if (!j->p) return PS_ERR_NO_DEVICE;
   *out_param_dev = j->p + j->blocks[block].flat_off;
   if (out_numel) *out_numel = j->blocks[block].numel;
@@ -878,6 +879,7 @@ int32_t ps_pull_momentum(ps_ctx* c, ps_job_t job, int32_t block, const float** o
   Job* j = find_job(c, job);
   if (!j) return PS_ERR_BAD_JOB;
   if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  if (j->blocks[block].owner == PS_OWNER_ELSEWHERE) return PS_ERR_NOT_OWNER;
   if (!j->v) return PS_ERR_NO_DEVICE;
   *out_mom_dev = j->v + j->blocks[block].flat_off;
   if (out_numel) *out_numel = j->blocks[block].numel;

@@ -668,3 +668,31 @@ def test_elastic_scenario_scheduler_migration_training(orc):
             assert ctxs[c].job_block_info(jid[c][ji], b).round == 4
     for c in ctxs:
         c.close()
+
+
+def test_non_finite_gradients_propagate_like_the_oracle(orc):
+    """NaN and infinities are not detected or cleaned: they propagate elementwise.
+    Where the oracle's result is NaN the GPU's must be NaN too (payloads are out
+    of contract); everywhere else the bits must match."""
+    n = 9001
+    s = spec([n], 3, lr=0.1, mu=0.9, wd=1e-4)
+    gpu = GpuService([s], 2)
+    o = OracleService(orc, [s], 2)
+    rng = np.random.default_rng(4)
+    g = [rng.normal(0, 1e-2, n).astype(F) for _ in range(3)]
+    g[0][[5, 4100, 9000]] = np.nan
+    g[1][[17, 4100]] = np.inf
+    g[2][[17, 8000]] = -np.inf          # +inf + -inf = NaN at 17; -inf alone at 8000
+    for w in range(3):
+        gpu.grads[0][w][:n].copy_(torch.from_numpy(g[w]))
+    for r in range(2):
+        gpu.step()
+        o.jobs[0].aggregate(0, g)
+    torch.cuda.synchronize()
+    for got, want in ((gpu.layer_param(0, 0).cpu().numpy(), o.jobs[0].p[0]),
+                      (gpu.layer_momentum(0, 0).cpu().numpy(), o.jobs[0].v[0])):
+        nan = np.isnan(want)
+        assert nan.sum() >= 4 and np.array_equal(np.isnan(got), nan)
+        assert np.array_equal(bits(got[~nan]), bits(want[~nan]))
+    assert np.isnan(gpu.svc.telemetry(gpu.jobs[0], 0).grad_norm2) and np.isnan(o.jobs[0].norm2[0])
+    gpu.close()

@@ -223,6 +223,9 @@ def test_ownership_states_on_the_host():
     with pytest.raises(PsError) as ei:
         b.push(jb, 0, 0, FAKE)
     assert ei.value.name == "PS_ERR_NOT_OWNER"
+    with pytest.raises(PsError) as ei:
+        b.pull(jb, 0)                                        # the owner answers pulls, not a shadow
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
     a.push(ja, 0, 0, FAKE)
     with pytest.raises(PsError) as ei:
         a.migrate_begin(ja, 0)                               # a push of the coming round is in
