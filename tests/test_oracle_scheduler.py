@@ -221,3 +221,38 @@ def test_scale_up_gives_a_slow_job_room():
     s3.scale_up_job(y)                           # 0 has 2 free: first 1.5 fits there, second (0.5 free) -> 1
     assert sorted(n for n, j, e in s3.where.values() if j == y) == [0, 1]
     assert sorted(s3.aggs) == [0, 1]
+
+
+def _golden(name):
+    import json
+    import os
+    return json.load(open(os.path.join(os.path.dirname(__file__), "golden", name)))
+
+
+def test_golden_toy_cyclic_execution():
+    """The figures the paper prints for its two-job example, from tests/golden/."""
+    g = _golden("toy_cyclic_execution.json")
+    for job, alone in zip(g["jobs"], g["cycle_alone"]):
+        s = SchedulerOracle()
+        s.assign(s.add_job(job["D"]), job["e"])
+        assert s.cycle(0) == alone
+    s = SchedulerOracle()
+    ids = [s.add_job(j["D"]) for j in g["jobs"]]
+    for i, j in zip(ids, g["jobs"]):
+        assert s.assign(i, j["e"])[1] == 0
+    assert s.cycle(0) == g["cycle_packed"]
+    runs = [sum(1 for _, js in s.cycle_plan(0) if i in js) for i in ids]
+    assert runs == g["runs_per_cycle_packed"]
+    assert s.busy(0) == g["derived"]["busy_packed"] and s.free(0) == g["derived"]["free_packed"]
+
+
+def test_golden_toy_loss_limit():
+    g = _golden("toy_loss_limit.json")
+    assert LOSS_LIMIT_DEFAULT == g["loss_limit_default"]
+    s = SchedulerOracle()
+    a, b = s.add_job(g["existing"]["D"]), s.add_job(g["arriving"]["D"])
+    s.assign(a, g["existing"]["e"])
+    d = iteration_duration(g["cycle_after"], g["existing"]["D"])
+    assert d == g["iteration_after"]
+    assert round(100 * loss(d, g["existing"]["D"])) == g["loss_percent_rounded"]
+    assert (s.estimate(0, b) is not None) == g["accepted_under_default_limit"]
