@@ -74,7 +74,19 @@ def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
     dt = time.perf_counter() - t0
     n_params = sum(w[1].size for w in work)
     n_bytes = sum((4 * w[3].W + 16) * w[1].size for w in work)
+    # second row: the same oracle function over the same blocks, one block per
+    # call, from a pool of threads (blocks are independent; ctypes drops the GIL)
+    from concurrent.futures import ThreadPoolExecutor
+    threads = max(1, min(16, os.cpu_count() or 1))
+    with ThreadPoolExecutor(threads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(lambda w: oracle.aggregate_block(w[0], w[1], w[2], w[3].lr, w[3].momentum,
+                                                       w[3].wd), work))
+        dt_all = time.perf_counter() - t0
     return {
+        "all_cores": {"value": n_params / dt_all, "unit": "params/s", "cores": threads,
+                      "GB_per_s": n_bytes / dt_all / 1e9, "seconds": dt_all,
+                      "note": "same oracle calls issued from a thread pool, one block per call"},
         "value": n_params / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
         "GB_per_s": n_bytes / dt / 1e9, "seconds": dt,
         "sample": f"every {k}-th block of the wave list: {len(work)} of {len(wave_refs)} blocks, "
@@ -132,6 +144,56 @@ def _cpu_model() -> str:
     return "unknown"
 
 
+def _per_wave_agg_ms(svc, step, n: int) -> dict:
+    """ps_agg_wave's GPU time of n further waves, one reading per wave (the
+    library reports sums, so each wave is the difference of two readings)."""
+    svc.timing_enable(True)
+    seen, each = 0.0, []
+    for _ in range(n):
+        step()
+        t = svc.timing_read().agg_ms
+        each.append(t - seen)
+        seen = t
+    svc.timing_enable(False)
+    each.sort()
+    return {"waves": n, "min": each[0], "median": each[len(each) // 2], "max": each[-1]}
+
+
+def _path_split(svc, gpu, specs, n: int) -> dict:
+    """Waves holding only the small-path blocks, and only the others, of the
+    same jobs: ps_agg_wave's GPU time of each, per wave (median of n)."""
+    from paper_2204_03211_amd.binding import WaveList
+
+    refs = {"small": [], "large": []}
+    grad_of = {}
+    for ji, j in enumerate(gpu.jobs):
+        for b in range(svc.job_n_blocks(j)):
+            info = svc.job_block_info(j, b)
+            refs["small" if info.small_path else "large"].append((j, b))
+            grad_of[(j, b)] = [g.data_ptr() + 4 * info.flat_offset for g in gpu.grads[ji]]
+    out = {}
+    for name, lst in refs.items():
+        if not lst:
+            out[name] = {"only_ms_per_wave": None}
+            continue
+        wave = WaveList(lst)
+        each = []
+        for i in range(n + 1):
+            for (j, b) in lst:
+                for w, ptr in enumerate(grad_of[(j, b)]):
+                    svc.push(j, b, w, ptr)
+            if i == 1:
+                svc.timing_enable(True)       # the first wave builds the plan: not read
+            svc.aggregate(wave)
+            if i >= 1:
+                t = svc.timing_read().agg_ms
+                each.append(t - sum(each))
+        svc.timing_enable(False)
+        each.sort()
+        out[name] = {"only_ms_per_wave": each[len(each) // 2]}
+    return out
+
+
 def measure(workload: str, args, keep: bool):
     """Time args.steps steps of one workload; returns (json object, service, last wave)."""
     import torch
@@ -176,6 +238,10 @@ def measure(workload: str, args, keep: bool):
     tm = svc.timing_read()
     svc.timing_enable(False)
 
+    # outside the timed region: the same step once more, read wave by wave
+    per_wave = _per_wave_agg_ms(svc, step, args.steps)
+    paths = _path_split(svc, gpu, specs, min(args.steps, 10))
+
     n_params = stats.n_params
     ms_per_step = dt / args.steps * 1e3
     value = n_params * args.steps / dt
@@ -213,8 +279,14 @@ def measure(workload: str, args, keep: bool):
             "ps_block_norms": tm.norms_ms / max(tm.n_waves, 1),
             "gpu_total": tm.total_ms / max(tm.n_waves, 1),
         },
+        "ps_agg_wave_ms_per_wave": per_wave,
         "small_path": {"blocks": stats.n_small_blocks, "bins": stats.n_small_bins,
-                       "params": stats.small_params},
+                       "params": stats.small_params,
+                       "algorithmic_bytes": stats.small_algorithmic_bytes, **paths["small"]},
+        "large_path": {"blocks": stats.n_blocks - stats.n_small_blocks, "tiles": stats.n_large_tiles,
+                       "params": stats.n_params - stats.small_params,
+                       "algorithmic_bytes": stats.algorithmic_bytes - stats.small_algorithmic_bytes,
+                       **paths["large"]},
         "setup_seconds": t_setup,
     }
     if not keep:
