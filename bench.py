@@ -239,8 +239,11 @@ def measure(workload: str, args, keep: bool):
     svc.timing_enable(False)
 
     # outside the timed region: the same step once more, read wave by wave
-    per_wave = _per_wave_agg_ms(svc, step, args.steps)
-    paths = _path_split(svc, gpu, specs, min(args.steps, 10))
+    if args.no_side_configs:
+        per_wave, paths = None, {"small": {}, "large": {}}
+    else:
+        per_wave = _per_wave_agg_ms(svc, step, args.steps)
+        paths = _path_split(svc, gpu, specs, min(args.steps, 10))
 
     n_params = stats.n_params
     ms_per_step = dt / args.steps * 1e3
@@ -305,7 +308,8 @@ def main() -> int:
     ap.add_argument("--workload", default="packed_wave")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-side-configs", action="store_true",
-                    help="skip the short single-job runs appended to the packed-wave line")
+                    help="only the timed steps: skip the wave-by-wave and per-path passes and the "
+                         "short single-job runs appended to the packed-wave line")
     ap.add_argument("--copy-calibration", action="store_true")
     ap.add_argument("--migration", action="store_true",
                     help="instead: time moving every block of --workload's first job to a second context")
