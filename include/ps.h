@@ -24,7 +24,8 @@
  *
  * Conventions
  *   - Every function returns a status (PS_OK = 0, errors negative) unless
- *     stated otherwise.  Nothing throws across this boundary.
+ *     stated otherwise.  Nothing throws across this boundary: a failed host
+ *     allocation inside the library comes back as PS_ERR_NOMEM.
  *   - "device" pointers address GPU memory of the current HIP device; "host"
  *     pointers address ordinary memory.  The library never takes ownership of a
  *     pointer passed in.

@@ -127,9 +127,12 @@ struct ps_sched {
   }
 };
 
+// No C++ exception leaves the library; see the same macro in ps_service.cpp.
+#define PS_NO_THROW catch (...) { return PS_ERR_NOMEM; }
+
 extern "C" {
 
-int32_t ps_sched_create(double loss_limit, ps_sched** out) {
+int32_t ps_sched_create(double loss_limit, ps_sched** out) try {
   if (!out) return PS_ERR_ARG;
   *out = nullptr;
   if (!(loss_limit < 1.0)) return PS_ERR_ARG;
@@ -138,18 +141,18 @@ int32_t ps_sched_create(double loss_limit, ps_sched** out) {
   if (loss_limit > 0) s->limit = loss_limit;
   *out = s;
   return PS_OK;
-}
+} PS_NO_THROW
 
 void ps_sched_destroy(ps_sched* s) { delete s; }
 
-int32_t ps_sched_add_job(ps_sched* s, double D, int32_t* out_job) {
+int32_t ps_sched_add_job(ps_sched* s, double D, int32_t* out_job) try {
   if (!s || !out_job || !(D > 0) || !std::isfinite(D)) return PS_ERR_ARG;
   s->D.push_back(D);
   *out_job = (int32_t)s->D.size() - 1;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_assign(ps_sched* s, int32_t job, double e, int32_t* out_task, int32_t* out_aggregator) {
+int32_t ps_sched_assign(ps_sched* s, int32_t job, double e, int32_t* out_task, int32_t* out_aggregator) try {
   if (!s || !(e > 0) || !std::isfinite(e)) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   int32_t n = s->choose(job, e, -1);
@@ -162,9 +165,9 @@ int32_t ps_sched_assign(ps_sched* s, int32_t job, double e, int32_t* out_task, i
   if (out_task) *out_task = id;
   if (out_aggregator) *out_aggregator = n;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_estimate(ps_sched* s, int32_t aggregator, int32_t job, double* out_cycle, double* out_free) {
+int32_t ps_sched_estimate(ps_sched* s, int32_t aggregator, int32_t job, double* out_cycle, double* out_free) try {
   if (!s) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   if (!s->agg_ok(aggregator)) return PS_ERR_BAD_BLOCK;
@@ -173,9 +176,9 @@ int32_t ps_sched_estimate(ps_sched* s, int32_t aggregator, int32_t job, double* 
   if (out_cycle) *out_cycle = C;
   if (out_free) *out_free = F;
   return 1;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int32_t cap, int32_t* out_n) {
+int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int32_t cap, int32_t* out_n) try {
   if (!s || cap < 0 || (cap > 0 && !out_released)) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   std::vector<int32_t> released;
@@ -209,9 +212,9 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
   if (out_n) *out_n = (int32_t)released.size();
   for (int32_t i = 0; i < (int32_t)released.size() && i < cap; ++i) out_released[i] = released[i];
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator) {
+int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator) try {
   if (!s) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   std::vector<int32_t> mine;
@@ -228,9 +231,9 @@ int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggrega
     if (a.live && a.by_job.empty()) a.live = false;
   if (out_new_aggregator) *out_new_aggregator = fresh;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_stats* out) {
+int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_stats* out) try {
   if (!s || !out) return PS_ERR_ARG;
   if (!s->agg_ok(aggregator)) return PS_ERR_BAD_BLOCK;
   const double C = s->cycle(aggregator);
@@ -241,9 +244,9 @@ int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_s
   out->n_tasks = 0;
   for (const auto& kv : s->aggs[aggregator].by_job) out->n_tasks += (int32_t)kv.second.size();
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_job_info(ps_sched* s, int32_t job, ps_sched_job_stats* out) {
+int32_t ps_sched_job_info(ps_sched* s, int32_t job, ps_sched_job_stats* out) try {
   if (!s || !out) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   const double D = s->D[job];
@@ -265,18 +268,18 @@ int32_t ps_sched_job_info(ps_sched* s, int32_t job, ps_sched_job_stats* out) {
   out->d = d;
   out->loss = lost(d, D);
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_task_info(ps_sched* s, int32_t task, int32_t* out_aggregator, int32_t* out_job, double* out_e) {
+int32_t ps_sched_task_info(ps_sched* s, int32_t task, int32_t* out_aggregator, int32_t* out_job, double* out_e) try {
   if (!s) return PS_ERR_ARG;
   if (task < 0 || (size_t)task >= s->tasks.size() || !s->tasks[task].live) return PS_ERR_BAD_BLOCK;
   if (out_aggregator) *out_aggregator = s->tasks[task].agg;
   if (out_job) *out_job = s->tasks[task].job;
   if (out_e) *out_e = s->tasks[task].e;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_sched_aggregators(ps_sched* s, int32_t* out_ids, int32_t cap, int32_t* out_n) {
+int32_t ps_sched_aggregators(ps_sched* s, int32_t* out_ids, int32_t cap, int32_t* out_n) try {
   if (!s || !out_n || cap < 0 || (cap > 0 && !out_ids)) return PS_ERR_ARG;
   int32_t k = 0;
   for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n)
@@ -286,10 +289,10 @@ int32_t ps_sched_aggregators(ps_sched* s, int32_t* out_ids, int32_t cap, int32_t
     }
   *out_n = k;
   return k > cap ? PS_ERR_CAPACITY : PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_sched_cycle_plan(ps_sched* s, int32_t aggregator, ps_sched_wave* out_waves, int32_t cap_waves,
-                            int32_t* out_n_waves, int32_t* out_jobs, int32_t cap_jobs, int32_t* out_n_jobs) {
+                            int32_t* out_n_waves, int32_t* out_jobs, int32_t cap_jobs, int32_t* out_n_jobs) try {
   if (!s || !out_n_waves || !out_n_jobs || cap_waves < 0 || cap_jobs < 0) return PS_ERR_ARG;
   if ((cap_waves > 0 && !out_waves) || (cap_jobs > 0 && !out_jobs)) return PS_ERR_ARG;
   if (!s->agg_ok(aggregator)) return PS_ERR_BAD_BLOCK;
@@ -324,7 +327,7 @@ int32_t ps_sched_cycle_plan(ps_sched* s, int32_t aggregator, ps_sched_wave* out_
   *out_n_waves = nw;
   *out_n_jobs = nj;
   return (nw > cap_waves || nj > cap_jobs) ? PS_ERR_CAPACITY : PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_sched_admit_late(double cycle, double elapsed, double remaining_scheduled, double e_late) {
   return (cycle - elapsed) - remaining_scheduled >= e_late ? 1 : 0;

@@ -295,7 +295,10 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
     // caller's launch_tiles) would make every later generation wait again
     const uint32_t resident = c->resident_tiles[ch.W <= PS_MAX_W ? ch.W : 0];
     const bool fits = resident == 0 || ch.end - ch.begin <= resident;
-    ch.hold_ticks = fits ? (uint32_t)(frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz) : 0u;
+    // never longer than half a millisecond, whatever the tables say: a resident
+    // launch reads for far less, and every wave must leave its wait soon
+    const double ticks = frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz;
+    ch.hold_ticks = fits ? (uint32_t)std::min(ticks, 5.0e-4 * c->clock_hz) : 0u;
   }
 
   P.stats.n_blocks = n;
@@ -362,6 +365,10 @@ size_t place(size_t* cursor, size_t count) {
 
 }  // namespace
 
+// No C++ exception leaves the library.  What this code can raise are failed
+// host allocations (containers growing), so that is what the caller is told.
+#define PS_NO_THROW catch (...) { return PS_ERR_NOMEM; }
+
 extern "C" {
 
 int32_t ps_version(void) { return 100; }
@@ -389,7 +396,7 @@ const char* ps_strerror(int32_t s) {
 
 const char* ps_last_error(ps_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
 
-int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) {
+int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) try {
   if (!out_ctx) return PS_ERR_ARG;
   *out_ctx = nullptr;
   ps_config n{};
@@ -408,7 +415,7 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) {
   }
   *out_ctx = c;
   return PS_OK;
-}
+} PS_NO_THROW
 
 void ps_destroy(ps_ctx* c) {
   if (!c) return;
@@ -430,7 +437,7 @@ void ps_destroy(ps_ctx* c) {
 }
 
 int32_t ps_job_arena_bytes(const ps_config* cfg, const int64_t* layer_numel, int32_t n_layers,
-                           uint64_t* out_bytes) {
+                           uint64_t* out_bytes) try {
   if (!out_bytes) return PS_ERR_ARG;
   ps_config n{};
   int32_t st = normalise_config(cfg, &n);
@@ -440,7 +447,7 @@ int32_t ps_job_arena_bytes(const ps_config* cfg, const int64_t* layer_numel, int
   if (st != PS_OK) return st;
   *out_bytes = (uint64_t)flat * 4 * 2;
   return PS_OK;
-}
+} PS_NO_THROW
 
 static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
                             float momentum, float wd, const float* const* init_params, void* stream,
@@ -512,19 +519,19 @@ static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_lay
 
 int32_t ps_register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W, float lr,
                         float momentum, float wd, const float* const* init_params, void* stream,
-                        ps_job_t* out_job, int32_t* out_n_blocks) {
+                        ps_job_t* out_job, int32_t* out_n_blocks) try {
   return register_job(c, layer_numel, n_layers, W, lr, momentum, wd, init_params, stream, out_job,
                       out_n_blocks, /*shadow=*/false);
-}
+} PS_NO_THROW
 
 int32_t ps_register_shadow_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_layers, int32_t W,
                                float lr, float momentum, float wd, void* stream, ps_job_t* out_job,
-                               int32_t* out_n_blocks) {
+                               int32_t* out_n_blocks) try {
   return register_job(c, layer_numel, n_layers, W, lr, momentum, wd, nullptr, stream, out_job,
                       out_n_blocks, /*shadow=*/true);
-}
+} PS_NO_THROW
 
-int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) {
+int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -545,23 +552,23 @@ int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) {
     if (o.live) top = std::max<uint64_t>(top, round_up(o.arena_off + o.arena_bytes, PS_ALIGN_BYTES));
   c->arena_top = top;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_job_n_blocks(ps_ctx* c, ps_job_t job) {
+int32_t ps_job_n_blocks(ps_ctx* c, ps_job_t job) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
   return j ? (int32_t)j->blocks.size() : PS_ERR_BAD_JOB;
-}
+} PS_NO_THROW
 
-int64_t ps_job_flat_numel(ps_ctx* c, ps_job_t job) {
+int64_t ps_job_flat_numel(ps_ctx* c, ps_job_t job) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
   return j ? j->flat_numel : (int64_t)PS_ERR_BAD_JOB;
-}
+} PS_NO_THROW
 
-int32_t ps_job_block_info(ps_ctx* c, ps_job_t job, int32_t block, ps_block_info* out) {
+int32_t ps_job_block_info(ps_ctx* c, ps_job_t job, int32_t block, ps_block_info* out) try {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -579,9 +586,9 @@ int32_t ps_job_block_info(ps_ctx* c, ps_job_t job, int32_t block, ps_block_info*
   out->owner = b.owner;
   out->reserved_ = 0;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const float* grad_dev) {
+int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const float* grad_dev) try {
   if (!c || !grad_dev) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -595,9 +602,9 @@ int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const fl
   b.grad[worker] = grad_dev;
   b.mask |= 1u << worker;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_flat_dev) {
+int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_flat_dev) try {
   if (!c || !grad_flat_dev) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -613,10 +620,10 @@ int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_
     b.mask |= bit;
   }
   return PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_ref* out, int64_t cap,
-                     int64_t* out_n) {
+                     int64_t* out_n) try {
   if (!c || !out_n || n_jobs < 0 || (n_jobs > 0 && !jobs) || cap < 0 || (cap > 0 && !out))
     return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
@@ -653,10 +660,10 @@ int32_t ps_pack_wave(ps_ctx* c, const ps_job_t* jobs, int32_t n_jobs, ps_block_r
     head[best] = bk + 1;
   }
   return PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_split_ready(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_block_ref* out_ready,
-                       int64_t* out_n_ready, ps_block_ref* out_late, int64_t* out_n_late) {
+                       int64_t* out_n_ready, ps_block_ref* out_late, int64_t* out_n_late) try {
   if (!c || !out_n_ready || !out_n_late) return PS_ERR_ARG;
   if (n > 0 && (!out_ready || !out_late)) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
@@ -671,9 +678,9 @@ int32_t ps_split_ready(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_block_
   *out_n_ready = nr;
   *out_n_late = nl;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_migrate_begin(ps_ctx* c, ps_job_t job, int32_t block) {
+int32_t ps_migrate_begin(ps_ctx* c, ps_job_t job, int32_t block) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -684,9 +691,9 @@ int32_t ps_migrate_begin(ps_ctx* c, ps_job_t job, int32_t block) {
   if (b.mask != 0) return PS_ERR_BUSY;  // pushes of the coming round are already in
   b.owner = PS_OWNER_LEAVING;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_migrate_cancel(ps_ctx* c, ps_job_t job, int32_t block) {
+int32_t ps_migrate_cancel(ps_ctx* c, ps_job_t job, int32_t block) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -696,10 +703,10 @@ int32_t ps_migrate_cancel(ps_ctx* c, ps_job_t job, int32_t block) {
   if (b.owner != PS_OWNER_LEAVING) return PS_ERR_NOT_OWNER;
   b.owner = PS_OWNER_HERE;
   return PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* dst, ps_job_t dst_job,
-                        void* stream) {
+                        void* stream) try {
   if (!src || !dst || src == dst) return PS_ERR_ARG;
   // both contexts change: take their locks in address order
   std::mutex& m1 = src < dst ? src->mu : dst->mu;
@@ -733,9 +740,9 @@ int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* ds
   bd.mask = 0;
   bs.owner = PS_OWNER_ELSEWHERE;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_stats* out) {
+int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_stats* out) try {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   const int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
@@ -743,9 +750,9 @@ int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_sta
   layout_plan(c, list, n, c->plan);
   *out = c->plan.stats;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) {
+int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
@@ -857,9 +864,9 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     j.stat_round[list[i].block] = b.round;
   }
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_dev, int64_t* out_numel) {
+int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_dev, int64_t* out_numel) try {
   if (!c || !out_param_dev) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -870,10 +877,10 @@ int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_
   *out_param_dev = j->p + j->blocks[block].flat_off;
   if (out_numel) *out_numel = j->blocks[block].numel;
   return PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_pull_momentum(ps_ctx* c, ps_job_t job, int32_t block, const float** out_mom_dev,
-                         int64_t* out_numel) {
+                         int64_t* out_numel) try {
   if (!c || !out_mom_dev) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -884,10 +891,10 @@ int32_t ps_pull_momentum(ps_ctx* c, ps_job_t job, int32_t block, const float** o
   *out_mom_dev = j->v + j->blocks[block].flat_off;
   if (out_numel) *out_numel = j->blocks[block].numel;
   return PS_OK;
-}
+} PS_NO_THROW
 
 int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const float** out_mom_dev,
-                     int64_t* out_flat_numel) {
+                     int64_t* out_flat_numel) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -897,9 +904,9 @@ int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const
   if (out_mom_dev) *out_mom_dev = j->v;
   if (out_flat_numel) *out_flat_numel = j->flat_numel;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_timing_enable(ps_ctx* c, int32_t on) {
+int32_t ps_timing_enable(ps_ctx* c, int32_t on) try {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
@@ -910,9 +917,9 @@ int32_t ps_timing_enable(ps_ctx* c, int32_t on) {
   c->timing = ps_timing{};
   c->timing_on = on != 0;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_timing_read(ps_ctx* c, ps_timing* out) {
+int32_t ps_timing_read(ps_ctx* c, ps_timing* out) try {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   for (TimingSet& t : c->tsets) {
@@ -921,9 +928,9 @@ int32_t ps_timing_read(ps_ctx* c, ps_timing* out) {
   }
   *out = c->timing;
   return PS_OK;
-}
+} PS_NO_THROW
 
-int32_t ps_telemetry(ps_ctx* c, ps_job_t job, int32_t block, ps_block_stats* out) {
+int32_t ps_telemetry(ps_ctx* c, ps_job_t job, int32_t block, ps_block_stats* out) try {
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   Job* j = find_job(c, job);
@@ -932,6 +939,6 @@ int32_t ps_telemetry(ps_ctx* c, ps_job_t job, int32_t block, ps_block_stats* out
   out->grad_norm2 = reinterpret_cast<volatile double*>(j->stat)[block];
   out->round = j->stat_round[block];
   return PS_OK;
-}
+} PS_NO_THROW
 
 }  // extern "C"
