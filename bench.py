@@ -127,9 +127,21 @@ def migration_bench(spec, reps: int):
     times, host = times[1:], host[1:]
     n_bytes = 8 * spec.n_params
     ms = sum(times) / len(times)
+    # the same move as one batched call
+    many = []
+    for _ in range(max(reps, 2)):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        svcs[src].migrate_many(jobs[src], list(range(nb)), svcs[1 - src], jobs[1 - src])
+        b.record()
+        torch.cuda.synchronize()
+        many.append(a.elapsed_time(b))
+        src = 1 - src
+    many_ms = sum(many[1:]) / len(many[1:])
     out = {"migration": True, "model": spec.model, "blocks": nb, "params": spec.n_params,
            "bytes_moved": n_bytes, "gpu_ms": ms, "host_call_ms": sum(host) / len(host),
-           "GB_per_s": n_bytes / ms / 1e6}
+           "GB_per_s": n_bytes / ms / 1e6,
+           "batched_gpu_ms": many_ms, "batched_GB_per_s": n_bytes / many_ms / 1e6}
     for s in svcs:
         s.close()
     return out

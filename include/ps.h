@@ -293,11 +293,24 @@ int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* o
  *                    the block from this call on and may take pushes at once; its
  *                    first ps_aggregate naming the block is ordered after the
  *                    copy on whatever stream it runs (TENSOR_COPY_DONE).  src
- *                    becomes PS_OWNER_ELSEWHERE. */
+ *                    becomes PS_OWNER_ELSEWHERE.  If the shard had itself
+ *                    arrived at src by a copy not yet waited for, the new copy
+ *                    is ordered after that one.
+ * ps_migrate_many    announce and copy n blocks (ids in blocks, host array) of
+ *                    one job in one call, e.g. a whole job when an Aggregator is
+ *                    recycled (Section 3.3.2).  Blocks may be owned or already
+ *                    announced; all are checked before any moves (same errors
+ *                    as above, PS_ERR_DUP_BLOCK for a repeated id; both jobs
+ *                    must have been registered with the same layers and block
+ *                    size, else PS_ERR_ARG).  Runs of consecutive block ids
+ *                    move as one copy per array, and the new owner waits on
+ *                    one event for all of them. */
 int32_t ps_migrate_begin(ps_ctx* ctx, ps_job_t job, int32_t block);
 int32_t ps_migrate_cancel(ps_ctx* ctx, ps_job_t job, int32_t block);
 int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* dst, ps_job_t dst_job,
                         void* stream);
+int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, int32_t n, ps_ctx* dst,
+                        ps_job_t dst_job, void* stream);
 
 /* --- measurement ------------------------------------------------------------ */
 

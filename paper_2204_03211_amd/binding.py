@@ -68,7 +68,7 @@ class Timing(C.Structure):
 
 EXPORTS = [
     "ps_create", "ps_destroy", "ps_job_arena_bytes", "ps_register_job", "ps_register_shadow_job",
-    "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy",
+    "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy", "ps_migrate_many",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
     "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat",
     "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
@@ -100,6 +100,7 @@ def load_library() -> C.CDLL:
     L.ps_migrate_begin.argtypes = [vp, i32, i32]
     L.ps_migrate_cancel.argtypes = [vp, i32, i32]
     L.ps_migrate_copy.argtypes = [vp, i32, i32, vp, i32, vp]
+    L.ps_migrate_many.argtypes = [vp, i32, C.POINTER(i32), i32, vp, i32, vp]
     L.ps_unregister_job.argtypes = [vp, i32]
     L.ps_job_n_blocks.argtypes = [vp, i32]
     L.ps_job_flat_numel.argtypes = [vp, i32]
@@ -248,6 +249,12 @@ class ParameterService:
                      stream: Optional[torch.cuda.Stream] = None) -> None:
         sp = _stream_ptr(stream) if self.arena is not None else None
         self._check(self.L.ps_migrate_copy(self.ctx, job, block, dst.ctx, dst_job, sp))
+
+    def migrate_many(self, job: int, blocks: Sequence[int], dst: "ParameterService", dst_job: int,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+        arr = (C.c_int32 * max(len(blocks), 1))(*blocks)
+        sp = _stream_ptr(stream) if self.arena is not None else None
+        self._check(self.L.ps_migrate_many(self.ctx, job, arr, len(blocks), dst.ctx, dst_job, sp))
 
     def unregister_job(self, job: int) -> None:
         self._check(self.L.ps_unregister_job(self.ctx, job))

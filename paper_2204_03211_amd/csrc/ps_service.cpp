@@ -26,6 +26,13 @@ constexpr uint64_t kAlignElems = PS_ALIGN_BYTES / 4;
 
 inline uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
+// The event that marks the arrival of migrated shard content.  One copy call
+// may bring many blocks; they share one event.
+struct Arrival {
+  hipEvent_t ev = nullptr;
+  int32_t refs = 0;
+};
+
 struct Block {
   int32_t layer;
   int64_t layer_off;
@@ -35,8 +42,7 @@ struct Block {
   uint32_t mask = 0;
   uint64_t wave_stamp = 0;  // id of the last list that named this block (duplicate check)
   uint8_t owner = PS_OWNER_HERE;   // PS_OWNER_*
-  bool ready_pending = false;      // shard content arrives by a copy: wait for `ready` first
-  hipEvent_t ready = nullptr;
+  Arrival* ready = nullptr;        // shard content arrives by a copy: wait for this first (else null)
   const float* grad[PS_MAX_W];
 };
 
@@ -115,6 +121,8 @@ struct ps_ctx {
   ps_timing timing{};
   double clock_hz = 1.0e8;      // rate of the device's wall clock
   int64_t n_ready_pending = 0;  // blocks whose migrated content has not been waited for yet
+  std::vector<Arrival*> arrivals;       // every arrival event ever created (owned)
+  std::vector<Arrival*> arrivals_free;  // those no block refers to
   uint32_t resident_tiles[PS_MAX_W + 1] = {};  // per W: workgroups the chip holds at once (0 = unknown)
 };
 
@@ -161,6 +169,38 @@ int32_t layout_layers(const int64_t* layer_numel, int32_t n_layers, int64_t cap_
 Job* find_job(ps_ctx* c, ps_job_t job) {
   if (job < 0 || (size_t)job >= c->jobs.size() || !c->jobs[job].live) return nullptr;
   return &c->jobs[job];
+}
+
+int32_t hip_fail(ps_ctx* c, hipError_t e, const char* what);
+
+Arrival* arrival_get(ps_ctx* c) {
+  if (!c->arrivals_free.empty()) {
+    Arrival* a = c->arrivals_free.back();
+    c->arrivals_free.pop_back();
+    return a;
+  }
+  Arrival* a = new Arrival();
+  if (hipEventCreateWithFlags(&a->ev, hipEventDisableTiming) != hipSuccess) {
+    delete a;
+    return nullptr;
+  }
+  c->arrivals.push_back(a);
+  return a;
+}
+
+// The block no longer needs its arrival event (it was waited for, or the block goes away).
+void arrival_drop(ps_ctx* c, Block& b) {
+  if (!b.ready) return;
+  if (--b.ready->refs == 0) c->arrivals_free.push_back(b.ready);
+  b.ready = nullptr;
+  c->n_ready_pending -= 1;
+}
+
+void arrival_attach(ps_ctx* c, Block& b, Arrival* a) {
+  arrival_drop(c, b);
+  b.ready = a;
+  a->refs += 1;
+  c->n_ready_pending += 1;
 }
 
 int32_t hip_fail(ps_ctx* c, hipError_t e, const char* what) {
@@ -433,6 +473,10 @@ void ps_destroy(ps_ctx* c) {
     if (j.stat && c->cfg.arena_dev) (void)hipHostFree(j.stat);
     else delete[] j.stat;
   }
+  for (Arrival* a : c->arrivals) {
+    (void)hipEventDestroy(a->ev);
+    delete a;
+  }
   delete c;
 }
 
@@ -537,10 +581,7 @@ int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) try {
   Job* j = find_job(c, job);
   if (!j) return PS_ERR_BAD_JOB;
   j->live = false;
-  for (Block& b : j->blocks) {
-    if (b.ready_pending) c->n_ready_pending -= 1;
-    if (b.ready) (void)hipEventDestroy(b.ready);
-  }
+  for (Block& b : j->blocks) arrival_drop(c, b);
   if (j->stat && c->cfg.arena_dev) (void)hipHostFree(j->stat);
   else delete[] j->stat;
   j->stat = nullptr;
@@ -727,18 +768,98 @@ int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* ds
   // the copy must see the source's last update of the shard, whatever stream ran it
   for (Slot& s : src->slots)
     if (s.in_flight && s.stream != hs) PS_HIP(src, hipStreamWaitEvent(hs, s.done, 0));
+  // ... and, if the shard itself came here by a copy nobody has waited for yet, that copy
+  if (bs.ready) {
+    PS_HIP(src, hipStreamWaitEvent(hs, bs.ready->ev, 0));
+    arrival_drop(src, bs);
+  }
   const size_t bytes = (size_t)bs.numel * 4;
   PS_HIP(dst, hipMemcpyAsync(jd->p + bd.flat_off, js->p + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
   PS_HIP(dst, hipMemcpyAsync(jd->v + bd.flat_off, js->v + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
-  if (!bd.ready) PS_HIP(dst, hipEventCreateWithFlags(&bd.ready, hipEventDisableTiming));
-  PS_HIP(dst, hipEventRecord(bd.ready, hs));
+  Arrival* a = arrival_get(dst);
+  if (!a) return PS_ERR_NOMEM;
+  const hipError_t er = hipEventRecord(a->ev, hs);
+  if (er != hipSuccess) {
+    dst->arrivals_free.push_back(a);
+    return hip_fail(dst, er, "recording the arrival of a migrated block");
+  }
   // the new owner may take pushes at once; its first update waits for the copy
-  if (!bd.ready_pending) dst->n_ready_pending += 1;
-  bd.ready_pending = true;
+  arrival_attach(dst, bd, a);
   bd.owner = PS_OWNER_HERE;
   bd.round = bs.round;
   bd.mask = 0;
   bs.owner = PS_OWNER_ELSEWHERE;
+  return PS_OK;
+} PS_NO_THROW
+
+int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, int32_t n, ps_ctx* dst,
+                        ps_job_t dst_job, void* stream) try {
+  if (!src || !dst || src == dst || n < 0 || (n > 0 && !blocks)) return PS_ERR_ARG;
+  std::mutex& m1 = src < dst ? src->mu : dst->mu;
+  std::mutex& m2 = src < dst ? dst->mu : src->mu;
+  std::lock_guard<std::mutex> g1(m1);
+  std::lock_guard<std::mutex> g2(m2);
+  Job* js = find_job(src, src_job);
+  Job* jd = find_job(dst, dst_job);
+  if (!js || !jd) return PS_ERR_BAD_JOB;
+  if (js->W != jd->W) return PS_ERR_ARG;
+  // all or nothing: check every block before anything moves
+  const uint64_t stamp = ++src->wave_counter;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t b = blocks[i];
+    if (b < 0 || (size_t)b >= js->blocks.size() || (size_t)b >= jd->blocks.size()) return PS_ERR_BAD_BLOCK;
+    Block& bs = js->blocks[b];
+    const Block& bd = jd->blocks[b];
+    if (bs.wave_stamp == stamp) return PS_ERR_DUP_BLOCK;
+    bs.wave_stamp = stamp;
+    if (bs.owner == PS_OWNER_ELSEWHERE || bd.owner != PS_OWNER_ELSEWHERE) return PS_ERR_NOT_OWNER;
+    if (bs.owner == PS_OWNER_HERE && bs.mask != 0) return PS_ERR_BUSY;
+    if (bs.numel != bd.numel || bs.flat_off != bd.flat_off) return PS_ERR_ARG;
+  }
+  if (n == 0) return PS_OK;
+  if (!js->p || !jd->p) return PS_ERR_NO_DEVICE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  for (Slot& s : src->slots)
+    if (s.in_flight && s.stream != hs) PS_HIP(src, hipStreamWaitEvent(hs, s.done, 0));
+  for (int32_t i = 0; i < n && src->n_ready_pending > 0; ++i) {
+    Block& bs = js->blocks[blocks[i]];
+    if (!bs.ready) continue;  // else the shard came here by a copy nobody has waited for yet
+    PS_HIP(src, hipStreamWaitEvent(hs, bs.ready->ev, 0));
+    arrival_drop(src, bs);
+  }
+  // Blocks with consecutive ids are neighbours in the flat layout (between two
+  // layers lies only padding that no block owns and that is zero on both sides):
+  // each run of consecutive ids moves with one copy per array.
+  std::vector<int32_t> ids(blocks, blocks + n);
+  std::sort(ids.begin(), ids.end());
+  for (size_t a = 0; a < ids.size();) {
+    size_t z = a;
+    while (z + 1 < ids.size() && ids[z + 1] == ids[z] + 1) ++z;
+    const Block& first = js->blocks[ids[a]];
+    const Block& last = js->blocks[ids[z]];
+    const size_t bytes = (size_t)(last.flat_off + last.numel - first.flat_off) * 4;
+    PS_HIP(dst, hipMemcpyAsync(jd->p + first.flat_off, js->p + first.flat_off, bytes,
+                               hipMemcpyDeviceToDevice, hs));
+    PS_HIP(dst, hipMemcpyAsync(jd->v + first.flat_off, js->v + first.flat_off, bytes,
+                               hipMemcpyDeviceToDevice, hs));
+    a = z + 1;
+  }
+  Arrival* arr = arrival_get(dst);
+  if (!arr) return PS_ERR_NOMEM;
+  const hipError_t er = hipEventRecord(arr->ev, hs);
+  if (er != hipSuccess) {
+    dst->arrivals_free.push_back(arr);
+    return hip_fail(dst, er, "recording the arrival of migrated blocks");
+  }
+  for (int32_t b : ids) {
+    Block& bs = js->blocks[b];
+    Block& bd = jd->blocks[b];
+    arrival_attach(dst, bd, arr);
+    bd.owner = PS_OWNER_HERE;
+    bd.round = bs.round;
+    bd.mask = 0;
+    bs.owner = PS_OWNER_ELSEWHERE;
+  }
   return PS_OK;
 } PS_NO_THROW
 
@@ -764,12 +885,13 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   // A shard that arrived by migration must not be updated before its copy is
   // complete (the new owner's consistency rule): order this stream after it.
   if (c->n_ready_pending > 0) {
+    const Arrival* waited = nullptr;  // blocks that came together sit together: skip repeats
     for (int64_t i = 0; i < n; ++i) {
       Block& b = c->jobs[list[i].job].blocks[list[i].block];
-      if (!b.ready_pending) continue;
-      PS_HIP(c, hipStreamWaitEvent(hs, b.ready, 0));
-      b.ready_pending = false;
-      c->n_ready_pending -= 1;
+      if (!b.ready) continue;
+      if (b.ready != waited) PS_HIP(c, hipStreamWaitEvent(hs, b.ready->ev, 0));
+      waited = b.ready;
+      arrival_drop(c, b);
     }
   }
 

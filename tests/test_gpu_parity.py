@@ -459,6 +459,78 @@ def test_migration_between_two_contexts_keeps_the_trajectory(orc):
     A.close(); B.close()
 
 
+def test_batched_migration_keeps_the_trajectory(orc):
+    """ps_migrate_many: every round a random set of blocks (runs of neighbours
+    and loners alike) changes sides in one call per direction, on a side stream
+    and unsynchronised; some hop there and straight back on another stream with
+    no update in between.  Values and round counters follow the oracle bit for bit."""
+    from paper_2204_03211_amd import OWNER_ELSEWHERE, ParameterService
+    s = spec([40_000, 100, 4097, 9000, 12], 3)
+    seed = 78
+    cap_bytes = 16 * 1024
+    need = ParameterService.job_arena_bytes(s.layer_numel, cap_bytes) + 256
+    dev = torch.device("cuda:0")
+    arenas = [torch.empty(need, dtype=torch.uint8, device=dev) for _ in range(2)]
+    ctx = [ParameterService(a, cap_bytes) for a in arenas]
+    init = [layer_values(seed, "param", (0, l), n, s.param_std, dev) for l, n in enumerate(s.layer_numel)]
+    ja, nb = ctx[0].register_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd, init)
+    jb, _ = ctx[1].register_shadow_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd)
+    job = [ja, jb]
+    infos = [ctx[0].job_block_info(ja, b) for b in range(nb)]
+    flat_n = ctx[0].job_flat_numel(ja)
+    grads = [torch.zeros(flat_n, dtype=torch.float32, device=dev) for _ in range(s.W)]
+    layer_flat = {i.layer: i.flat_offset for i in infos if i.layer_offset == 0}
+    o = OracleService(orc, [s], seed, cap_elems=cap_bytes // 4)
+    side, third = torch.cuda.Stream(), torch.cuda.Stream()
+    side_of = [0] * nb
+    rng = np.random.default_rng(5)
+    for r in range(6):
+        for w in range(s.W):
+            for l, n in enumerate(s.layer_numel):
+                wl.fill_normal_like(grads[w][layer_flat[l]:layer_flat[l] + n],
+                                    wl.stream_key(seed, "grad", 0, w, r, l), s.grad_std)
+        torch.cuda.synchronize()
+        for k in (0, 1):
+            for w in range(s.W):
+                ctx[k].push_flat(job[k], w, grads[w])        # each side takes the blocks it owns
+        ctx[0].aggregate(ctx[0].pack_wave([ja]))
+        with torch.cuda.stream(side):
+            ctx[1].aggregate(ctx[1].pack_wave([jb]))
+        o.step(r)
+        torch.cuda.synchronize()
+        if r == 2:                                           # the whole job in one call
+            chosen = list(range(nb))
+        else:
+            start = int(rng.integers(0, nb - 4))
+            chosen = sorted(set(range(start, start + 4)) | set(int(x) for x in rng.choice(nb, 3, replace=False)))
+        lists = [[b for b in chosen if side_of[b] == k] for k in (0, 1)]
+        for k in (0, 1):
+            lst = lists[k]
+            rng.shuffle(lst)
+            ctx[k].migrate_many(job[k], lst, ctx[1 - k], job[1 - k], stream=side)
+            for b in lst:
+                side_of[b] = 1 - k
+                assert ctx[k].job_block_info(job[k], b).owner == OWNER_ELSEWHERE
+                assert ctx[1 - k].job_block_info(job[1 - k], b).round == r + 1
+        # two of them hop straight back, on a third stream: ordered after their arrival
+        back = chosen[:2]
+        for b in back:
+            k = side_of[b]
+            ctx[k].migrate_many(job[k], [b], ctx[1 - k], job[1 - k], stream=third)
+            side_of[b] = 1 - k
+    torch.cuda.synchronize()
+    assert 0 < sum(side_of) < nb
+    for b in range(nb):
+        k = side_of[b]
+        layer, off, n = o.jobs[0].blocks[b]
+        assert np.array_equal(bits(ctx[k].pull(job[k], b).cpu().numpy()), bits(o.jobs[0].p[layer][off:off + n])), b
+        assert np.array_equal(bits(ctx[k].pull_momentum(job[k], b).cpu().numpy()),
+                              bits(o.jobs[0].v[layer][off:off + n])), b
+        assert ctx[k].job_block_info(job[k], b).round == 6
+    for c in ctx:
+        c.close()
+
+
 def test_big_blocks_and_wide_jobs(orc):
     """A 16 MiB block cap (one 5 M-element block: offsets far beyond one launch),
     W = 32 on a multi-tile layer, and W = 1."""

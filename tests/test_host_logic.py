@@ -253,6 +253,40 @@ def test_ownership_states_on_the_host():
         a.migrate_cancel(ja, 1)
 
 
+def test_batched_migration_checks_everything_before_anything_moves():
+    a, b = ParameterService(None, max_block_bytes=1024), ParameterService(None, max_block_bytes=1024)
+    ja, nb = reg(a, [1000, 10, 300], W=2)                     # 4 + 1 + 2 blocks
+    jb, _ = b.register_shadow_job([1000, 10, 300], 2, 0.1, 0.9, 1e-4)
+    assert nb == 7
+    a.migrate_many(ja, [], b, jb)                            # nothing to do is fine
+    for bad, name in (([0, 7], "PS_ERR_BAD_BLOCK"), ([1, 2, 1], "PS_ERR_DUP_BLOCK"), ([-1], "PS_ERR_BAD_BLOCK")):
+        with pytest.raises(PsError) as ei:
+            a.migrate_many(ja, bad, b, jb)
+        assert ei.value.name == name
+    a.push(ja, 3, 1, FAKE)
+    with pytest.raises(PsError) as ei:
+        a.migrate_many(ja, [2, 3], b, jb)                    # block 3 has a push pending
+    assert ei.value.name == "PS_ERR_BUSY"
+    with pytest.raises(PsError) as ei:
+        b.migrate_many(jb, [0], a, ja)                       # b owns nothing
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+    a.migrate_begin(ja, 5)                                   # already announced blocks may be listed
+    with pytest.raises(PsError) as ei:
+        a.migrate_many(ja, [0, 1, 5], b, jb)                 # valid list, but no device behind these contexts
+    assert ei.value.name == "PS_ERR_NO_DEVICE"
+    from paper_2204_03211_amd import OWNER_HERE, OWNER_LEAVING
+    assert [a.job_block_info(ja, k).owner for k in range(7)] == [OWNER_HERE] * 5 + [OWNER_LEAVING, OWNER_HERE]
+    # a shadow with another block size or other layers is not the same job
+    c = ParameterService(None, max_block_bytes=2048)
+    jc, _ = c.register_shadow_job([1000, 10, 300], 2, 0.1, 0.9, 1e-4)
+    with pytest.raises(PsError) as ei:
+        a.migrate_many(ja, [0], c, jc)
+    assert ei.value.name == "PS_ERR_ARG"
+    with pytest.raises(PsError) as ei:
+        a.migrate_many(ja, [0], a, ja)
+    assert ei.value.name == "PS_ERR_ARG"
+
+
 def test_pushes_from_many_threads():
     """One context, one mutex: W worker threads push their gradients for every
     block at the same time; every mask ends up complete and nothing is lost."""
