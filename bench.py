@@ -160,16 +160,18 @@ def _cpu_model() -> str:
 def _per_wave_agg_ms(svc, step, n: int) -> dict:
     """ps_agg_wave's GPU time of n further waves, one reading per wave (the
     library reports sums, so each wave is the difference of two readings)."""
-    svc.timing_enable(True)
+    svc.timing_enable(2)                          # every phase: four events a wave
     seen, each = 0.0, []
     for _ in range(n):
         step()
-        t = svc.timing_read().agg_ms
-        each.append(t - seen)
-        seen = t
-    svc.timing_enable(False)
+        tm = svc.timing_read()
+        each.append(tm.agg_ms - seen)
+        seen = tm.agg_ms
+    svc.timing_enable(0)
     each.sort()
-    return {"waves": n, "min": each[0], "median": each[len(each) // 2], "max": each[-1]}
+    return {"waves": n, "min": each[0], "median": each[len(each) // 2], "max": each[-1],
+            "phases_mean": {"upload": tm.upload_ms / n, "ps_agg_wave": tm.agg_ms / n,
+                            "ps_block_norms": tm.norms_ms / n, "gpu_total": tm.total_ms / n}}
 
 
 def _path_split(svc, gpu, specs, n: int) -> dict:
@@ -196,12 +198,12 @@ def _path_split(svc, gpu, specs, n: int) -> dict:
                 for w, ptr in enumerate(grad_of[(j, b)]):
                     svc.push(j, b, w, ptr)
             if i == 1:
-                svc.timing_enable(True)       # the first wave builds the plan: not read
+                svc.timing_enable(1)          # the first wave builds the plan: not read
             svc.aggregate(wave)
             if i >= 1:
                 t = svc.timing_read().agg_ms
                 each.append(t - sum(each))
-        svc.timing_enable(False)
+        svc.timing_enable(0)
         each.sort()
         out[name] = {"only_ms_per_wave": each[len(each) // 2]}
     return out
@@ -241,7 +243,7 @@ def measure(workload: str, args, keep: bool):
     svc.aggregate(svc.pack_wave(gpu.jobs))                   # consume the pushes again
     torch.cuda.synchronize()
 
-    svc.timing_enable(True)
+    svc.timing_enable(1)                          # two events a wave, around the aggregation launches
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -249,7 +251,7 @@ def measure(workload: str, args, keep: bool):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     tm = svc.timing_read()
-    svc.timing_enable(False)
+    svc.timing_enable(0)
 
     # outside the timed region: the same step once more, read wave by wave
     if args.no_side_configs:
@@ -290,11 +292,7 @@ def measure(workload: str, args, keep: bool):
             "note": "avg_launch_ms = HIP-event time from the first to the last launch of a wave "
                     "divided by the launches in it, so gaps between launches count",
         },
-        "kernels_ms_per_wave": {
-            "upload": tm.upload_ms / max(tm.n_waves, 1), "ps_agg_wave": agg_ms_wave,
-            "ps_block_norms": tm.norms_ms / max(tm.n_waves, 1),
-            "gpu_total": tm.total_ms / max(tm.n_waves, 1),
-        },
+        "ps_agg_wave_ms_per_wave_timed": agg_ms_wave,
         "ps_agg_wave_ms_per_wave": per_wave,
         "small_path": {"blocks": stats.n_small_blocks, "bins": stats.n_small_bins,
                        "params": stats.small_params,

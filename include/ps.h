@@ -314,9 +314,12 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
 
 /* --- measurement ------------------------------------------------------------ */
 
-/* on != 0: from now on every ps_aggregate brackets its copy and each of its
- * kernels with HIP events on the wave's stream, and the elapsed times are
- * summed per kind.  Resets the sums.  on == 0 stops it. */
+/* Event timing of the waves, for measurement.  on == 1: from now on every
+ * ps_aggregate brackets its aggregation launches with two HIP events on the
+ * wave's stream (agg_ms; upload_ms and norms_ms stay 0 and total_ms = agg_ms).
+ * on == 2: four events, so that the table upload and the telemetry reduction
+ * are timed too.  Each event costs the stream a few microseconds.  The elapsed
+ * times are summed per kind.  Resets the sums.  on == 0 stops it. */
 int32_t ps_timing_enable(ps_ctx* ctx, int32_t on);
 /* Wait for every wave this context has enqueued, then report the sums. */
 int32_t ps_timing_read(ps_ctx* ctx, ps_timing* out);

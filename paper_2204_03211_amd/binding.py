@@ -323,7 +323,7 @@ class ParameterService:
         return out
 
     def timing_enable(self, on: bool) -> None:
-        self._check(self.L.ps_timing_enable(self.ctx, 1 if on else 0))
+        self._check(self.L.ps_timing_enable(self.ctx, int(on)))
 
     def timing_read(self) -> Timing:
         out = Timing()

@@ -67,6 +67,7 @@ struct Job {
 struct TimingSet {
   hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
   bool pending = false;
+  bool all_phases = false;  // four events recorded (else only ev[1], ev[2] around the launches)
   int64_t launches = 0;
 };
 constexpr int kTimingSets = 8;
@@ -117,7 +118,7 @@ struct ps_ctx {
   Plan plan;                     // scratch of ps_plan_wave
   std::vector<uint64_t> sig;     // scratch: signature of the list being validated
   std::string last_error;
-  bool timing_on = false;
+  int32_t timing_level = 0;     // 0 off, 1 aggregation launches only, 2 every phase
   ps_timing timing{};
   double clock_hz = 1.0e8;      // rate of the device's wall clock
   int64_t n_ready_pending = 0;  // blocks whose migrated content has not been waited for yet
@@ -358,17 +359,21 @@ int32_t slot_retire(ps_ctx* c, Slot& s) {
 // Wait for a measured wave and add its event times to the sums.
 int32_t timing_harvest(ps_ctx* c, TimingSet& t) {
   if (!t.pending) return PS_OK;
-  PS_HIP(c, hipEventSynchronize(t.ev[3]));
+  PS_HIP(c, hipEventSynchronize(t.ev[t.all_phases ? 3 : 2]));
   t.pending = false;
-  float ms[3] = {0, 0, 0};
-  for (int i = 0; i < 3; ++i) PS_HIP(c, hipEventElapsedTime(&ms[i], t.ev[i], t.ev[i + 1]));
-  float tot = 0;
-  PS_HIP(c, hipEventElapsedTime(&tot, t.ev[0], t.ev[3]));
+  float agg = 0;
+  PS_HIP(c, hipEventElapsedTime(&agg, t.ev[1], t.ev[2]));
+  float up = 0, norms = 0, tot = agg;
+  if (t.all_phases) {
+    PS_HIP(c, hipEventElapsedTime(&up, t.ev[0], t.ev[1]));
+    PS_HIP(c, hipEventElapsedTime(&norms, t.ev[2], t.ev[3]));
+    PS_HIP(c, hipEventElapsedTime(&tot, t.ev[0], t.ev[3]));
+  }
   c->timing.n_waves += 1;
   c->timing.n_launches += t.launches;
-  c->timing.upload_ms += ms[0];
-  c->timing.agg_ms += ms[1];
-  c->timing.norms_ms += ms[2];
+  c->timing.upload_ms += up;
+  c->timing.agg_ms += agg;
+  c->timing.norms_ms += norms;
   c->timing.total_ms += tot;
   return PS_OK;
 }
@@ -909,14 +914,15 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     }
   }
   TimingSet* ts = nullptr;
-  if (c->timing_on) {
+  if (c->timing_level > 0) {
     ts = &c->tsets[c->next_tset];
     c->next_tset = (c->next_tset + 1) % kTimingSets;
     st = timing_harvest(c, *ts);
     if (st != PS_OK) return st;
     for (hipEvent_t& e : ts->ev)
       if (!e) PS_HIP(c, hipEventCreate(&e));
-    PS_HIP(c, hipEventRecord(ts->ev[0], hs));
+    ts->all_phases = c->timing_level >= 2;
+    if (ts->all_phases) PS_HIP(c, hipEventRecord(ts->ev[0], hs));
   }
   if (!reuse) {
     c->next_slot = (c->last_slot + 1) % kSlots;
@@ -962,6 +968,7 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   Slot& s = *sp;
   PsWaveTables t = s.tables;
   for (int i = 0; i < 3; ++i) t.ev[i] = ts ? ts->ev[i + 1] : nullptr;
+  if (ts && !ts->all_phases) t.ev[2] = nullptr;
   const int le = ps_launch_wave(t, stream);
   if (le != 0) {
     s.valid = false;
@@ -1037,7 +1044,7 @@ int32_t ps_timing_enable(ps_ctx* c, int32_t on) try {
     if (st != PS_OK) return st;
   }
   c->timing = ps_timing{};
-  c->timing_on = on != 0;
+  c->timing_level = on <= 0 ? 0 : (on >= 2 ? 2 : 1);
   return PS_OK;
 } PS_NO_THROW
 
