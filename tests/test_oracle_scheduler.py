@@ -256,3 +256,47 @@ def test_golden_toy_loss_limit():
     assert d == g["iteration_after"]
     assert round(100 * loss(d, g["existing"]["D"])) == g["loss_percent_rounded"]
     assert (s.estimate(0, b) is not None) == g["accepted_under_default_limit"]
+
+
+def test_failed_drain_leaves_everything_where_it_was():
+    """Recycling moves the largest task first; if a later one finds no room the
+    tasks already moved go back (Section 3.3.2: recycle only if every task fits
+    without new allocations)."""
+    s = SchedulerOracle()
+    a, b, k = s.add_job(10.0), s.add_job(10.0), s.add_job(10.0)
+    s._place(s.allocate(), a, 6.0)              # load 0.6, 4 free
+    n1 = s.allocate()
+    t3 = s._place(n1, b, 3.0)
+    t25 = s._place(n1, b, 2.5)                  # load 0.55: the one to drain
+    s._place(s.allocate(), k, 1.0)
+    before = dict(s.where)
+    del before[max(before)]                     # k's task leaves with k
+    assert s.remove_job(k) == [2]               # 3.0 fits into 0, then 2.5 does not (1 free): undone
+    assert s.where == before and s.where[t3][0] == n1 and s.where[t25][0] == n1
+    assert s.busy(0) == 6.0 and s.busy(1) == 5.5
+    assert sorted(e for _, e in s.aggs[1].tasks[b]) == [2.5, 3.0] and list(s.aggs[0].tasks) == [a]
+
+
+def test_equally_loaded_aggregators_the_younger_one_goes():
+    s = SchedulerOracle()
+    k, a, b = s.add_job(10.0), s.add_job(10.0), s.add_job(10.0)
+    s._place(s.allocate(), k, 5.0)
+    s._place(s.allocate(), a, 3.0)
+    s._place(s.allocate(), b, 3.0)
+    assert s.remove_job(k) == [0, 2]            # 0 is empty; 1 and 2 tie at 0.3: 2 drains into 1
+    assert sorted(s.aggs) == [1] and s.busy(1) == 6.0
+
+
+def test_drained_tasks_never_land_on_the_aggregator_being_drained():
+    """The Aggregator being recycled can itself be the tightest fit for its own
+    task (short cycle, little free time); it is not a destination."""
+    s = SchedulerOracle()
+    k, fast, slow = s.add_job(10.0), s.add_job(4.0), s.add_job(20.0)
+    s._place(s.allocate(), k, 1.0)
+    s._place(s.allocate(), fast, 1.0)           # cycle 4, load 0.25, 3 free
+    s._place(s.allocate(), slow, 6.0)           # cycle 20, load 0.3, 14 free
+    released = s.remove_job(k)
+    assert released == [0, 1]
+    assert sorted(s.aggs) == [2]
+    assert all(n in s.aggs for n, _, _ in s.where.values())
+    assert sorted(s.aggs[2].tasks) == [fast, slow] and s.busy(2) == 5 * 1.0 + 6.0
