@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per ps_agg_wave launch from rocprofv3 FETCH_SIZE + WRITE_SIZE counters
 # (scaled by a 1 GiB copy), for the default configuration of a workload.  Only
 # valid for the kernel as profiled: set an entry to None when the kernel changes.
-MEASURED_TRAFFIC_PER_LAUNCH = {"packed_wave": 33.966e9 / 125, "vgg16": 6.6494e9 / 19,
-                               "resnet50": 2.0465e9 / 4, "alexnet": 2.9366e9 / 9}
+MEASURED_TRAFFIC_PER_LAUNCH = {"packed_wave": 33.966e9 / 110, "vgg16": 6.6493e9 / 17,
+                               "resnet50": 2.0465e9 / 4, "alexnet": 2.9365e9 / 8}
 
 
 def specs_for(name: str):

@@ -96,7 +96,7 @@ typedef struct ps_config {
                                  PS_ERR_NO_DEVICE */
   uint64_t arena_bytes;
   uint32_t launch_tiles;      /* tiles (4096 values each) per kernel launch of the large-block
-                                 path; 0 = as many as the chip holds at once (1792 on MI355X);
+                                 path; 0 = as many as the chip holds at once (2048 on MI355X);
                                  a larger value switches the store hold off for that launch */
   int32_t store_hold_permille; /* a launch's workgroups keep their results in registers and
                                  store them only once this fraction (in 1/1000) of the

@@ -60,13 +60,15 @@ constexpr uint32_t PS_WG = 256;                 // threads per workgroup (4 wave
 #define PS_TILE_U 4
 #endif
 #ifndef PS_LOAD_G
-#define PS_LOAD_G 3
+#define PS_LOAD_G 2   // workers whose loads are in flight together: 62 VGPRs, 8 waves per SIMD
 #endif
 constexpr uint32_t PS_TILE_QUADS_PER_LANE = PS_TILE_U;  // 16-byte accesses per lane per stream in a tile
 constexpr uint32_t PS_TILE_ELEMS = PS_WG * 4 * PS_TILE_QUADS_PER_LANE;
 constexpr uint32_t PS_BIN_MAX_BLOCKS = 64;
 constexpr uint32_t PS_BIN_MAX_QUADS = 1024;  // >= quads of the largest small-path block
-constexpr uint32_t PS_BIN_MAX_PTRS = 1024;
+// The bin tables sit in LDS (19 264 bytes a workgroup with these sizes); 8
+// workgroups per CU must fit in the CU's 160 KiB, or the large path loses residency.
+constexpr uint32_t PS_BIN_MAX_PTRS = 768;
 constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path accepts
 
 // Tiles per launch of the large path, by worker count.  HBM serves pure reads

@@ -193,6 +193,9 @@ __device__ __forceinline__ void small_bin(const unsigned char* __restrict__ recs
   __shared__ uint32_t ps[PS_BIN_MAX_BLOCKS + 1];   // first pointer of each entry
   __shared__ const float* sptr[PS_BIN_MAX_PTRS];
   __shared__ double qpart[PS_BIN_MAX_QUADS];
+  static_assert(sizeof(PsBlockRec) * PS_BIN_MAX_BLOCKS + 4 * PS_BIN_MAX_BLOCKS + 8 * (PS_BIN_MAX_BLOCKS + 1) +
+                        8 * PS_BIN_MAX_PTRS + 8 * PS_BIN_MAX_QUADS + 8 * (PS_WG / 64) <= 160 * 1024 / 8,
+                "eight workgroups of this kernel must fit in one CU's LDS");
 
   const uint32_t tid = threadIdx.x;
   const uint32_t count = bin.count, quads = bin.quads, nptrs = bin.nptrs;
