@@ -254,6 +254,50 @@ def test_full_size_single_job_configs(orc, model):
     gpu.close()
 
 
+def test_job_larger_than_four_gib_sampled_blocks(orc):
+    """One job of 1.2 G parameters in two layers (4.8 GB per array: byte offsets
+    inside the job pass 2^32), W = 2, two rounds with the same gradients.  The
+    oracle recomputes the blocks around the 4 GiB mark, the first and last
+    blocks of both layers and a few in between."""
+    layers = [1_100_000_123, 100_000_007]
+    s = spec(layers, 2)
+    gpu = GpuService([s], 21)
+    gpu.fill_grads(0)
+    job = gpu.jobs[0]
+    wave = gpu.wave()
+    nb = gpu.svc.job_n_blocks(job)
+    assert nb == -(-layers[0] // (1 << 20)) + -(-layers[1] // (1 << 20))
+    mark = (1 << 32) // 4                                    # element whose byte offset is 4 GiB
+    pick = {0, 1, nb - 1, nb - 2, nb // 3}
+    for b in range(nb):
+        _, _, n, flat = gpu.blocks[0][b]
+        if flat <= mark + (1 << 20) and flat + n >= mark - (1 << 20):
+            pick.add(b)
+        if n != 1 << 20:
+            pick.add(b)                                      # the two ragged tails
+    pick = sorted(pick)
+    assert 8 <= len(pick) <= 16
+    state = {}
+    for b in pick:
+        layer, off, n, _ = gpu.blocks[0][b]
+        p = layer_values(21, "param", (0, layer), n, s.param_std, "cuda:0", start=off).cpu().numpy()
+        g = [layer_values(21, "grad", (0, w, 0, layer), n, s.grad_std, "cuda:0", start=off).cpu().numpy()
+             for w in range(s.W)]
+        state[b] = (p, np.zeros(n, F), g)
+    for r in range(2):
+        gpu.step(wave)
+    torch.cuda.synchronize()
+    for b in pick:
+        p, v, g = state[b]
+        for r in range(2):
+            n2 = orc.aggregate_block(g, p, v, s.lr, s.momentum, s.wd)
+        assert np.array_equal(bits(gpu.svc.pull(job, b).cpu().numpy()), bits(p)), b
+        assert np.array_equal(bits(gpu.svc.pull_momentum(job, b).cpu().numpy()), bits(v)), b
+        st = gpu.svc.telemetry(job, b)
+        assert st.round == 2 and st.grad_norm2 == pytest.approx(n2, rel=1e-12)
+    gpu.close()
+
+
 def test_full_size_packed_wave_sampled_blocks(orc):
     """The twelve-job wave at full size (1743 blocks, 900 M parameters, W per
     job from {2,4,8,16}) in the launch configuration the benchmark times; two
