@@ -102,7 +102,7 @@ typedef struct ps_config {
                                  store them only once this fraction (in 1/1000) of the
                                  launch's predicted read time has passed since they
                                  started, so that reads and writes reach HBM in separate
-                                 bursts; 0 = default (900), negative = no hold, at most 2000 */
+                                 bursts; 0 = default (1000), negative = no hold, at most 2000 */
 } ps_config;
 
 typedef struct ps_block_ref {
@@ -200,8 +200,10 @@ int32_t ps_job_block_info(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_inf
 
 /* --- push (worker -> service) -------------------------------------------- */
 
-/* Record worker's gradient for (job, block) for the block's current round.
- * grad_dev: DEVICE pointer to numel floats, 16-byte aligned, owned by the
+/* The paper's Push (Section 2: after the backward pass of a tensor each worker
+ * pushes its gradient of that tensor to the server; Appendix A: the request
+ * carries the key and the worker).  Records worker's gradient for (job, block)
+ * for the block's current round.  grad_dev: DEVICE pointer to numel floats, 16-byte aligned, owned by the
  * caller; it is read, never written, by the aggregation that consumes it and
  * must stay valid and unchanged until that aggregation has completed on its
  * stream.  No data is copied.  Errors: BAD_JOB, BAD_BLOCK, BAD_WORKER,
@@ -242,17 +244,27 @@ int32_t ps_plan_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, ps_
 
 /* --- aggregate (the hot path) --------------------------------------------- */
 
-/* Aggregate every block of block_list (host array of n entries): sum the W
- * pushed gradients in worker order and apply the update to the block's
- * parameter and momentum shards, on stream.  All-or-nothing: the whole list is
- * validated first (BAD_JOB, BAD_BLOCK, NOT_READY, DUP_BLOCK) and nothing is
- * launched or changed on error.  On success every listed block's push mask is
- * cleared and its round advances by one.  n = 0 is a no-op. */
+/* Model aggregation (Section 2: once a tensor's gradients are in from all
+ * workers the server aggregates them and updates the master copy with the
+ * result; Section 3.1: one Aggregator serves the aggregations of many jobs; the
+ * list is one cycle's worth of them, Section 3.3.1).  Aggregates every block of
+ * block_list (host array of n entries): sums the W pushed gradients in worker
+ * order and applies the update to the block's parameter and momentum shards, on
+ * stream.  All-or-nothing: the whole list is validated first (BAD_JOB,
+ * BAD_BLOCK, DUP_BLOCK, NOT_OWNER, NOT_READY if a block lacks a push: the
+ * paper's aggregation is synchronous) and nothing is launched or changed on
+ * error; NO_DEVICE on a planning context; HIP if the runtime refuses a call.
+ * On success every listed block's push mask is cleared and its round advances
+ * by one.  n = 0 is a no-op.  The launch tables of the previous call are reused
+ * when the list and the pushed pointers are the same as then.  Waves on
+ * different streams that touch the same block must be ordered by the caller. */
 int32_t ps_aggregate(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, void* stream);
 
 /* --- pull (service -> worker) and inspection ------------------------------- */
 
-/* Borrowed DEVICE pointers to the block's parameters / momentum.  They stay
+/* The paper's Pull (Section 2: workers fetch the updated parameters before the
+ * next iteration).  Borrowed DEVICE pointers to the block's parameters /
+ * momentum: no copy is made, the worker reads the master copy in place.  They stay
  * valid until the job is unregistered; their contents are those of the last
  * aggregation enqueued for the block, in stream order.  A block that has
  * migrated away (PS_OWNER_ELSEWHERE) is PS_ERR_NOT_OWNER: pull from its new
