@@ -276,7 +276,7 @@ def measure(workload: str, args, keep: bool):
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": workload, "jobs": len(specs), "W": [s.W for s in specs],
-            "models": [s.model for s in specs], "blocks": stats.n_blocks, "params": n_params,
+            "job_shapes": [s.model for s in specs], "blocks": stats.n_blocks, "params": n_params,
             "block_cap_bytes": 4 << 20, "seed": seed,
             "algorithmic_bytes_per_step": stats.algorithmic_bytes,
         },
