@@ -14,7 +14,7 @@
 #include "../../paper_2204_03211_amd/csrc/ps_internal.h"
 
 int ps_launch_wave(const PsWaveTables&, void*) { return 0; }
-uint32_t ps_resident_workgroups(uint32_t) { return 1792; }
+uint32_t ps_resident_workgroups(uint32_t) { return 2048; }
 
 #define CHECK(x) do { if (!(x)) { std::printf("CHECK failed: %s (line %d)\n", #x, __LINE__); std::exit(1); } } while (0)
 
@@ -69,6 +69,32 @@ static void service_rounds(uint64_t seed) {
     CHECK(ps_plan_wave(ctx, l.data(), (int64_t)l.size(), &st) == PS_ERR_DUP_BLOCK);
     l.back().block = 1 << 30;
     CHECK(ps_plan_wave(ctx, l.data(), (int64_t)l.size(), &st) == PS_ERR_BAD_BLOCK);
+  }
+  // migration bookkeeping against a second planning context (stops at the device)
+  {
+    ps_ctx* other = nullptr;
+    CHECK(ps_create(&cfg, &other) == PS_OK);
+    std::vector<int64_t> layers = {5000, 7, 300};
+    ps_job_t a = -1, b = -1;
+    int32_t nb = 0, nb2 = 0;
+    CHECK(ps_register_job(ctx, layers.data(), 3, 2, 0.1f, 0.9f, 0.0f, nullptr, nullptr, &a, &nb) == PS_OK);
+    CHECK(ps_register_shadow_job(other, layers.data(), 3, 2, 0.1f, 0.9f, 0.0f, nullptr, &b, &nb2) == PS_OK);
+    CHECK(nb == nb2 && nb >= 3);
+    std::vector<int32_t> ids((size_t)nb);
+    for (int32_t i = 0; i < nb; ++i) ids[(size_t)i] = i;
+    std::shuffle(ids.begin(), ids.end(), rng);
+    CHECK(ps_migrate_begin(ctx, a, ids[0]) == PS_OK);
+    CHECK(ps_migrate_begin(ctx, a, ids[0]) == PS_ERR_NOT_OWNER);
+    CHECK(ps_migrate_many(ctx, a, ids.data(), nb, other, b, nullptr) == PS_ERR_NO_DEVICE);
+    CHECK(ps_migrate_copy(ctx, a, ids[0], other, b, nullptr) == PS_ERR_NO_DEVICE);
+    CHECK(ps_migrate_cancel(ctx, a, ids[0]) == PS_OK);
+    ids.push_back(ids[1]);
+    CHECK(ps_migrate_many(ctx, a, ids.data(), nb + 1, other, b, nullptr) == PS_ERR_DUP_BLOCK);
+    CHECK(ps_push(ctx, a, ids[2], 1, reinterpret_cast<const float*>(uintptr_t(1) << 20)) == PS_OK);
+    CHECK(ps_migrate_many(ctx, a, ids.data(), nb, other, b, nullptr) == PS_ERR_BUSY);
+    CHECK(ps_migrate_many(other, b, ids.data(), 1, ctx, a, nullptr) == PS_ERR_NOT_OWNER);
+    CHECK(ps_unregister_job(other, b) == PS_OK);
+    ps_destroy(other);
   }
   if (n_jobs > 1) CHECK(ps_unregister_job(ctx, jobs[0]) == PS_OK);
   ps_destroy(ctx);
