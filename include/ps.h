@@ -141,6 +141,11 @@ typedef struct ps_wave_stats {
   uint64_t algorithmic_bytes; /* sum over blocks of (4 W + 16) * numel */
   uint64_t small_algorithmic_bytes; /* the part of that in small-path blocks */
   int64_t n_launches;      /* aggregation kernel launches the list is cut into */
+  double est_seconds;      /* predicted GPU time of the wave on MI355X: per launch, bytes read
+                              at 7.0 TB/s, then bytes written at 6.0 TB/s, plus 1.5 us; plus
+                              5 us a wave.  Within a few per cent of the measured time for
+                              waves of tens of megabytes and more; an execution time e_t for
+                              ps_sched_assign (the paper's profiler, Section 3.3.1) */
 } ps_wave_stats;
 
 typedef struct ps_timing {
@@ -241,6 +246,10 @@ int32_t ps_split_ready(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n,
 /* Validate a block list exactly as ps_aggregate would, and report how it would
  * be laid out on the GPU.  Changes no state, touches no device. */
 int32_t ps_plan_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, ps_wave_stats* out);
+
+/* The same report for a list whose pushes need not be in yet (ids, duplicates
+ * and ownership are still checked): what a wave of these blocks would cost. */
+int32_t ps_estimate_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, ps_wave_stats* out);
 
 /* --- aggregate (the hot path) --------------------------------------------- */
 

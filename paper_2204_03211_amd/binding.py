@@ -58,7 +58,8 @@ class WaveStats(C.Structure):
     _fields_ = [("n_blocks", C.c_int64), ("n_params", C.c_int64), ("n_large_tiles", C.c_int64),
                 ("n_small_blocks", C.c_int64), ("n_small_bins", C.c_int64),
                 ("small_params", C.c_int64), ("algorithmic_bytes", C.c_uint64),
-                ("small_algorithmic_bytes", C.c_uint64), ("n_launches", C.c_int64)]
+                ("small_algorithmic_bytes", C.c_uint64), ("n_launches", C.c_int64),
+                ("est_seconds", C.c_double)]
 
 
 class Timing(C.Structure):
@@ -68,7 +69,8 @@ class Timing(C.Structure):
 
 EXPORTS = [
     "ps_create", "ps_destroy", "ps_job_arena_bytes", "ps_register_job", "ps_register_shadow_job",
-    "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy", "ps_migrate_many",
+    "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy",
+    "ps_migrate_many", "ps_estimate_wave",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
     "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat",
     "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
@@ -110,6 +112,7 @@ def load_library() -> C.CDLL:
     L.ps_push_flat.argtypes = [vp, i32, i32, vp]
     L.ps_pack_wave.argtypes = [vp, P(i32), i32, P(BlockRef), i64, P(i64)]
     L.ps_plan_wave.argtypes = [vp, P(BlockRef), i64, P(WaveStats)]
+    L.ps_estimate_wave.argtypes = [vp, P(BlockRef), i64, P(WaveStats)]
     L.ps_aggregate.argtypes = [vp, P(BlockRef), i64, vp]
     L.ps_pull.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_momentum.argtypes = [vp, i32, i32, P(vp), P(i64)]
@@ -295,6 +298,11 @@ class ParameterService:
     def plan_wave(self, wave: WaveList) -> WaveStats:
         out = WaveStats()
         self._check(self.L.ps_plan_wave(self.ctx, wave.arr, wave.n, C.byref(out)))
+        return out
+
+    def estimate_wave(self, wave: WaveList) -> WaveStats:
+        out = WaveStats()
+        self._check(self.L.ps_estimate_wave(self.ctx, wave.arr, wave.n, C.byref(out)))
         return out
 
     def aggregate(self, wave: WaveList, stream: Optional[torch.cuda.Stream] = None) -> None:

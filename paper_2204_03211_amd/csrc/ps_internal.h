@@ -83,6 +83,11 @@ inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e
 // loads, many streams); used only to predict when a launch's reads end.
 constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
 constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 1000;
+// For the predicted time of a wave (ps_wave_stats.est_seconds): sustained
+// pure-write rate in resident-size launches, and the fitted fixed costs.
+constexpr double PS_WRITE_BYTES_PER_SEC = 6.0e12;
+constexpr double PS_EST_LAUNCH_SECONDS = 1.5e-6;
+constexpr double PS_EST_WAVE_SECONDS = 5.0e-6;
 
 struct PsWaveTables {
   const unsigned char* recs;     // PsBlockRec records

@@ -342,6 +342,17 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
     ch.hold_ticks = fits ? (uint32_t)std::min(ticks, 5.0e-4 * c->clock_hz) : 0u;
   }
 
+  // predicted GPU time of the wave: each launch reads, then writes (the store
+  // hold separates the two), plus a fixed cost per launch and per wave
+  double est = PS_EST_WAVE_SECONDS;
+  for (const PsChunk& ch : P.chunks) {
+    const double params = (double)ch.read_bytes / (4.0 * ch.W + 8.0);
+    est += (double)ch.read_bytes / PS_READ_BYTES_PER_SEC + 8.0 * params / PS_WRITE_BYTES_PER_SEC +
+           PS_EST_LAUNCH_SECONDS;
+  }
+  if (P.chunks.empty() && !P.bins.empty()) est += PS_EST_LAUNCH_SECONDS;
+  P.stats.est_seconds = n > 0 ? est : 0.0;
+
   P.stats.n_blocks = n;
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
   P.stats.n_small_bins = (int64_t)P.bins.size();
@@ -872,6 +883,16 @@ int32_t ps_plan_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_sta
   if (!c || !out) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   const int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
+  if (st != PS_OK) return st;
+  layout_plan(c, list, n, c->plan);
+  *out = c->plan.stats;
+  return PS_OK;
+} PS_NO_THROW
+
+int32_t ps_estimate_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave_stats* out) try {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  const int32_t st = validate_list(c, list, n, /*need_pushes=*/false);
   if (st != PS_OK) return st;
   layout_plan(c, list, n, c->plan);
   *out = c->plan.stats;

@@ -254,6 +254,32 @@ def test_full_size_single_job_configs(orc, model):
     gpu.close()
 
 
+@pytest.mark.parametrize("model", ["alexnet", "resnet50", "vgg16"])
+def test_predicted_wave_time_is_close_to_the_measured_one(model):
+    """ps_wave_stats.est_seconds against HIP-event time of the aggregation
+    launches, full-size single jobs.  Not a parity check: a sanity bound on the
+    cost model the scheduler is fed with (boxes differ by a few per cent)."""
+    s = wl.job_config(model)
+    gpu = GpuService([s], 0)
+    gpu.fill_grads(0)
+    wave = gpu.wave()
+    for _ in range(3):
+        gpu.step(wave)
+    torch.cuda.synchronize()
+    gpu.push_all()
+    est = gpu.svc.plan_wave(wave).est_seconds
+    gpu.svc.aggregate(wave)
+    gpu.svc.timing_enable(1)
+    for _ in range(10):
+        gpu.step(wave)
+    tm = gpu.svc.timing_read()
+    gpu.svc.timing_enable(0)
+    measured = tm.agg_ms / tm.n_waves * 1e-3
+    assert tm.n_waves == 10
+    assert est == pytest.approx(measured, rel=0.12), (est, measured)
+    gpu.close()
+
+
 def test_job_larger_than_four_gib_sampled_blocks(orc):
     """One job of 1.2 G parameters in two layers (4.8 GB per array: byte offsets
     inside the job pass 2^32), W = 2, two rounds with the same gradients.  The

@@ -287,6 +287,30 @@ def test_batched_migration_checks_everything_before_anything_moves():
     assert ei.value.name == "PS_ERR_ARG"
 
 
+def test_predicted_wave_time_follows_the_byte_model():
+    """est_seconds = sum over launches of read/7.0e12 + written/6.0e12 + 1.5 us, plus
+    5 us a wave; ps_estimate_wave reports it before any push is in."""
+    svc = ParameterService(None)
+    W, n = 8, 3 * (1 << 20) + 5000
+    j, nb = reg(svc, [n, 100], W=W)
+    wave = svc.pack_wave([j])
+    with pytest.raises(PsError) as ei:
+        svc.plan_wave(wave)                                   # no pushes yet
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    st = svc.estimate_wave(wave)
+    large = n                                                 # the 100-element layer rides in a bin
+    want = 5e-6 + st.n_launches * 1.5e-6 + (4 * W + 8) * large * 4 / 4 / 7.0e12 + 8 * large / 6.0e12
+    assert st.n_launches == 1 and st.n_small_blocks == 1
+    assert st.est_seconds == pytest.approx(want, rel=1e-9)
+    assert svc.estimate_wave(WaveList([])).est_seconds == 0.0
+    for w in range(W):
+        svc.push_flat(j, w, FAKE)
+    assert svc.plan_wave(wave).est_seconds == st.est_seconds
+    # one block at a time: what a scheduler would use as the task's execution time
+    each = [svc.estimate_wave(WaveList([(j, b)])).est_seconds for b in range(nb)]
+    assert all(e > 5e-6 for e in each) and each[0] == each[1] > each[3]
+
+
 def test_pushes_from_many_threads():
     """One context, one mutex: W worker threads push their gradients for every
     block at the same time; every mask ends up complete and nothing is lost."""

@@ -125,3 +125,25 @@ def test_assignment_rate_is_job_event_scale():
         s.assign(jobs[i % len(jobs)], 0.05 + (i % 7) * 0.01)
     dt = time.perf_counter() - t0
     assert dt < 5.0 and len(s.aggregators()) >= 2
+
+
+def test_predicted_wave_times_as_execution_times():
+    """The profiler's role (Section 3.3.1): a task's execution time comes from
+    the service's own prediction of the wave, here for whole jobs at full size on
+    a planning context.  VGG-16 (1.0 ms) and AlexNet (0.44 ms) share an
+    Aggregator whose cycle is 1.5 ms; ResNet-50 (0.30 ms) no longer fits."""
+    import workloads as wl
+    from paper_2204_03211_amd import ParameterService
+    svc = ParameterService(None)
+    sch = Scheduler()
+    placed = {}
+    for name in ("vgg16", "alexnet", "resnet50"):
+        s = wl.job_config(name)
+        j, _ = svc.register_job(s.layer_numel, s.W, s.lr, s.momentum, s.wd)
+        e_ms = svc.estimate_wave(svc.pack_wave([j])).est_seconds * 1e3
+        placed[name] = (e_ms, sch.assign(sch.add_job(1.5), e_ms)[1])
+    assert placed["vgg16"][0] == pytest.approx(1.0, rel=0.03)
+    assert placed["alexnet"][0] == pytest.approx(0.44, rel=0.03)
+    assert placed["resnet50"][0] == pytest.approx(0.30, rel=0.03)
+    assert [placed[n][1] for n in ("vgg16", "alexnet", "resnet50")] == [0, 0, 1]
+    svc.close()
