@@ -141,6 +141,65 @@ def test_any_order_and_any_partition_of_a_wave(orc):
     ref.close(); alt.close()
 
 
+def test_late_pushes_wait_at_most_one_cycle(orc):
+    """Late requests (Section 3.3.1, "Handling Outliers"): every round one worker's
+    push of a few blocks arrives after the cycle's wave was built.  The wave takes
+    the ready blocks; the stragglers are admitted into the same cycle when the
+    rule finds room and wait for the next one otherwise -- in both cases they are
+    aggregated before the job's next pushes, so the job is delayed by at most one
+    cycle and its trajectory equals the oracle's."""
+    from paper_2204_03211_amd import Scheduler
+    specs = [spec([30_000, 100, 4097], 4), spec([64, 20_000], 2)]
+    seed, cap = 12, 16 * 1024
+    gpu = GpuService(specs, seed, max_block_bytes=cap)
+    o = OracleService(orc, specs, seed, cap_elems=cap // 4)
+    rng = np.random.default_rng(1)
+    same_cycle = next_cycle = 0
+    carried = []                                            # blocks waiting for the next cycle
+    for r in range(5):
+        gpu.fill_grads(r)
+        refs = gpu.wave().tolist()
+        late_blocks = set(int(x) for x in rng.choice(len(refs), size=3, replace=False))
+        held = []
+        for i, (j, b) in enumerate(refs):
+            ji = gpu.jobs.index(j)
+            _, _, n, flat = gpu.blocks[ji][b]
+            for w in range(specs[ji].W):
+                if i in late_blocks and w == specs[ji].W - 1:
+                    held.append((j, b, w, gpu.grads[ji][w][flat:flat + n]))
+                else:
+                    gpu.svc.push(j, b, w, gpu.grads[ji][w][flat:flat + n])
+        ready, late = gpu.svc.split_ready(gpu.wave())
+        assert sorted(late.tolist()) == sorted(refs[i] for i in late_blocks)
+        with pytest.raises(PsError) as ei:
+            gpu.svc.aggregate(gpu.wave())                   # never a partial sum
+        assert ei.value.name == "PS_ERR_NOT_READY"
+        gpu.svc.aggregate(ready)
+        for j, b, w, g in held:                             # the stragglers' pushes arrive
+            gpu.svc.push(j, b, w, g)
+        # the rule: cycle 10, the wave took 6; room for a late request of 1.5 only while 2.5 is left
+        elapsed = 6.0
+        for ref in late.tolist():
+            if Scheduler.admit_late(10.0, elapsed, 0.0, 1.5):
+                gpu.svc.aggregate(WaveList([ref]))
+                elapsed += 1.5
+                same_cycle += 1
+            else:
+                carried.append(ref)
+                next_cycle += 1
+        # next cycle starts: whoever waited goes first, before any new push of its job
+        if carried:
+            gpu.svc.aggregate(WaveList(carried))
+            carried = []
+        o.step(r)
+    assert same_cycle == 10 and next_cycle == 5             # two fit (6 + 1.5 + 1.5 <= 10), the third waits
+    assert_state_equal(gpu, o, "late pushes")
+    for ji, j in enumerate(gpu.jobs):
+        for b in range(gpu.svc.job_n_blocks(j)):
+            assert gpu.svc.job_block_info(j, b).round == 5
+    gpu.close()
+
+
 def test_special_values_denormals_and_signed_zero(orc):
     """Hand-placed gradients: denormals, signed zeros, cancellation, the order
     and no-fma cases of the oracle's pins -- pushed through both kernels."""
