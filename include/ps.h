@@ -283,6 +283,14 @@ int32_t ps_pull(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_para
 int32_t ps_pull_momentum(ps_ctx* ctx, ps_job_t job, int32_t block, const float** out_mom_dev,
                          int64_t* out_numel);
 
+/* Pull as a copy: enqueue on stream a device-to-device copy of the block's
+ * parameters into dst_dev (DEVICE, numel floats, owned by the caller) -- the
+ * stand-in for the paper's server-to-worker transfer when a worker wants its own
+ * replica.  Ordered after updates enqueued on the same stream (and after the
+ * arrival of a shard that has just migrated here); updates running on other
+ * streams are the caller's to order.  Errors as ps_pull, PS_ERR_HIP. */
+int32_t ps_pull_copy(ps_ctx* ctx, ps_job_t job, int32_t block, float* dst_dev, void* stream);
+
 /* Base DEVICE pointers of the job's flat parameter and momentum arrays
  * (ps_job_flat_numel floats each; block b starts at flat_offset).  Regions of
  * blocks this context does not own hold stale or unset data. */

@@ -72,7 +72,7 @@ EXPORTS = [
     "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy",
     "ps_migrate_many", "ps_estimate_wave",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
-    "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat",
+    "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat", "ps_pull_copy",
     "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
 ]
 
@@ -117,6 +117,7 @@ def load_library() -> C.CDLL:
     L.ps_pull.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_momentum.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_flat.argtypes = [vp, i32, P(vp), P(vp), P(i64)]
+    L.ps_pull_copy.argtypes = [vp, i32, i32, vp, vp]
     L.ps_telemetry.argtypes = [vp, i32, i32, P(BlockStats)]
     L.ps_timing_enable.argtypes = [vp, i32]
     L.ps_timing_read.argtypes = [vp, P(Timing)]
@@ -314,6 +315,13 @@ class ParameterService:
         ptr, n = C.c_void_p(), C.c_int64()
         self._check(self.L.ps_pull(self.ctx, job, block, C.byref(ptr), C.byref(n)))
         return self._view(ptr.value, n.value)
+
+    def pull_copy(self, job: int, block: int, dst: torch.Tensor,
+                  stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Copy the block's parameters into dst (CUDA float32, at least numel elements)."""
+        sp = _stream_ptr(stream) if self.arena is not None else None
+        ptr = dst.data_ptr() if isinstance(dst, torch.Tensor) else int(dst)
+        self._check(self.L.ps_pull_copy(self.ctx, job, block, ptr, sp))
 
     def pull_momentum(self, job: int, block: int) -> torch.Tensor:
         ptr, n = C.c_void_p(), C.c_int64()

@@ -1043,6 +1043,22 @@ int32_t ps_pull_momentum(ps_ctx* c, ps_job_t job, int32_t block, const float** o
   return PS_OK;
 } PS_NO_THROW
 
+int32_t ps_pull_copy(ps_ctx* c, ps_job_t job, int32_t block, float* dst_dev, void* stream) try {
+  if (!c || !dst_dev) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  Job* j = find_job(c, job);
+  if (!j) return PS_ERR_BAD_JOB;
+  if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
+  const Block& b = j->blocks[block];
+  if (b.owner == PS_OWNER_ELSEWHERE) return PS_ERR_NOT_OWNER;
+  if (!j->p) return PS_ERR_NO_DEVICE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  // a shard that came by migration and has not been updated here yet: its copy must have landed
+  if (b.ready) PS_HIP(c, hipStreamWaitEvent(hs, b.ready->ev, 0));
+  PS_HIP(c, hipMemcpyAsync(dst_dev, j->p + b.flat_off, (size_t)b.numel * 4, hipMemcpyDeviceToDevice, hs));
+  return PS_OK;
+} PS_NO_THROW
+
 int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const float** out_mom_dev,
                      int64_t* out_flat_numel) try {
   if (!c) return PS_ERR_ARG;

@@ -141,6 +141,33 @@ def test_any_order_and_any_partition_of_a_wave(orc):
     ref.close(); alt.close()
 
 
+def test_pull_copy_hands_out_the_updated_parameters(orc):
+    """ps_pull_copy on the wave's stream, enqueued right after the update and not
+    synchronised in between: the copy holds the round's new parameters."""
+    s = spec([20_000, 100, 4097], 4)
+    gpu = GpuService([s], 31, max_block_bytes=16 * 1024)
+    o = OracleService(orc, [s], 31, cap_elems=4096)
+    job = gpu.jobs[0]
+    nb = gpu.svc.job_n_blocks(job)
+    side = torch.cuda.Stream()
+    outs = [torch.full((gpu.blocks[0][b][2] + 8,), 7.0, device="cuda:0") for b in range(nb)]
+    for r in range(2):
+        gpu.fill_grads(r)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            gpu.step()
+            for b in range(nb):
+                gpu.svc.pull_copy(job, b, outs[b], stream=side)
+        o.step(r)
+    torch.cuda.synchronize()
+    for b in range(nb):
+        layer, off, n = o.jobs[0].blocks[b]
+        got = outs[b].cpu().numpy()
+        assert np.array_equal(bits(got[:n]), bits(o.jobs[0].p[layer][off:off + n])), b
+        assert (got[n:] == 7.0).all()                        # nothing past the block is written
+    gpu.close()
+
+
 def test_late_pushes_wait_at_most_one_cycle(orc):
     """Late requests (Section 3.3.1, "Handling Outliers"): every round one worker's
     push of a few blocks arrives after the cycle's wave was built.  The wave takes

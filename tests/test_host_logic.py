@@ -287,6 +287,20 @@ def test_batched_migration_checks_everything_before_anything_moves():
     assert ei.value.name == "PS_ERR_ARG"
 
 
+def test_pull_copy_checks_before_it_touches_the_device():
+    a, b = ParameterService(None), ParameterService(None)
+    ja, _ = reg(a, [5000, 10], W=2)
+    jb, _ = b.register_shadow_job([5000, 10], 2, 0.1, 0.9, 1e-4)
+    for args, name in (((ja, 5, FAKE), "PS_ERR_BAD_BLOCK"), ((99, 0, FAKE), "PS_ERR_BAD_JOB"),
+                       ((ja, 0, 0), "PS_ERR_ARG"), ((ja, 0, FAKE), "PS_ERR_NO_DEVICE")):
+        with pytest.raises(PsError) as ei:
+            a.pull_copy(*args)
+        assert ei.value.name == name
+    with pytest.raises(PsError) as ei:
+        b.pull_copy(jb, 0, FAKE)                              # a shadow holds nothing to copy
+    assert ei.value.name == "PS_ERR_NOT_OWNER"
+
+
 def test_predicted_wave_time_follows_the_byte_model():
     """est_seconds = sum over launches of read/7.0e12 + written/6.0e12 + 1.5 us, plus
     5 us a wave; ps_estimate_wave reports it before any push is in."""
