@@ -194,7 +194,10 @@ int32_t ps_register_shadow_job(ps_ctx* ctx, const int64_t* layer_numel, int32_t 
                                int32_t* out_n_blocks);
 
 /* Forget a job.  Its arena space is reused only if it was the most recently
- * registered live job (the arena is a stack).  Pending pushes are dropped. */
+ * registered live job (the arena is a stack).  Pending pushes are dropped.
+ * Waves that name the job must have completed (synchronise their streams first):
+ * the job's telemetry memory is released here and its arena space may be handed
+ * to the next registration. */
 int32_t ps_unregister_job(ps_ctx* ctx, ps_job_t job);
 
 /* Number of blocks / flat elements (with padding) of a job; negative = error. */
