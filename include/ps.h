@@ -335,7 +335,7 @@ int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* o
  *                    as above, PS_ERR_DUP_BLOCK for a repeated id; both jobs
  *                    must have been registered with the same layers and block
  *                    size, else PS_ERR_ARG).  Runs of consecutive block ids
- *                    move as one copy per array, and the new owner waits on
+ *                    move in one kernel launch, and the new owner waits on
  *                    one event for all of them. */
 int32_t ps_migrate_begin(ps_ctx* ctx, ps_job_t job, int32_t block);
 int32_t ps_migrate_cancel(ps_ctx* ctx, ps_job_t job, int32_t block);

@@ -115,4 +115,10 @@ uint32_t ps_resident_workgroups(uint32_t W);
 // hipError_t value (0 = success).
 int ps_launch_wave(const PsWaveTables& t, void* stream);
 
+// Enqueue on stream the copy of n floats of parameters and n floats of momentum
+// (both pairs 16-byte aligned) from one context's shards to another's: the
+// TENSOR_COPY of a migration.  Returns a hipError_t value (0 = success).
+int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
+                   void* stream);
+
 #endif  // PS_INTERNAL_H_

@@ -317,6 +317,37 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
   if (lane == 0) *d->stat = a;
 }
 
+// ---------------------------------------------------------------------------
+// Migration copy: a workgroup moves one tile (PS_TILE_ELEMS floats) of the
+// parameter array and the same tile of the momentum array.  All eight loads of
+// a lane are issued before its first store; ragged ends are left to the buffer
+// range check.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict__ src_p,
+                                                        float* __restrict__ dst_p,
+                                                        const float* __restrict__ src_v,
+                                                        float* __restrict__ dst_v,
+                                                        unsigned long long n) {
+  constexpr int U = PS_TILE_QUADS_PER_LANE;
+  const unsigned long long at = (unsigned long long)blockIdx.x * PS_TILE_ELEMS;  // < n by the grid's size
+  const unsigned long long left = n - at;
+  const uint32_t bytes = (uint32_t)(left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
+  const uint32_t tid = threadIdx.x;
+  const __amdgpu_buffer_rsrc_t sp = span(src_p + at, bytes), sv = span(src_v + at, bytes);
+  const __amdgpu_buffer_rsrc_t dp = span(dst_p + at, bytes), dv = span(dst_v + at, bytes);
+  f32x4 a[U], b[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    a[u] = load4(sp, (u * PS_WG + tid) * 16);
+    b[u] = load4(sv, (u * PS_WG + tid) * 16);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    store4(dp, (u * PS_WG + tid) * 16, a[u]);
+    store4(dv, (u * PS_WG + tid) * 16, b[u]);
+  }
+}
+
 template <int W, bool FMA>
 void launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
                 uint32_t n_bins, uint32_t hold_ticks) {
@@ -370,6 +401,16 @@ uint32_t ps_resident_workgroups(uint32_t W) {
     case 16: return resident_of<16>(cus);
     default: return resident_of<0>(cus);
   }
+}
+
+int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
+                   void* stream_) {
+  if (n == 0) return 0;
+  const uint64_t tiles = (n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
+  if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(ps_copy_shards, dim3((uint32_t)tiles), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_),
+                     src_p, dst_p, src_v, dst_v, (unsigned long long)n);
+  return (int)hipGetLastError();
 }
 
 int ps_launch_wave(const PsWaveTables& t, void* stream_) {

@@ -789,9 +789,11 @@ int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* ds
     PS_HIP(src, hipStreamWaitEvent(hs, bs.ready->ev, 0));
     arrival_drop(src, bs);
   }
-  const size_t bytes = (size_t)bs.numel * 4;
-  PS_HIP(dst, hipMemcpyAsync(jd->p + bd.flat_off, js->p + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
-  PS_HIP(dst, hipMemcpyAsync(jd->v + bd.flat_off, js->v + bs.flat_off, bytes, hipMemcpyDeviceToDevice, hs));
+  {
+    const int le = ps_launch_copy(js->p + bs.flat_off, jd->p + bd.flat_off, js->v + bs.flat_off,
+                                  jd->v + bd.flat_off, (uint64_t)bs.numel, stream);
+    if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
+  }
   Arrival* a = arrival_get(dst);
   if (!a) return PS_ERR_NOMEM;
   const hipError_t er = hipEventRecord(a->ev, hs);
@@ -854,10 +856,9 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
     const Block& first = js->blocks[ids[a]];
     const Block& last = js->blocks[ids[z]];
     const size_t bytes = (size_t)(last.flat_off + last.numel - first.flat_off) * 4;
-    PS_HIP(dst, hipMemcpyAsync(jd->p + first.flat_off, js->p + first.flat_off, bytes,
-                               hipMemcpyDeviceToDevice, hs));
-    PS_HIP(dst, hipMemcpyAsync(jd->v + first.flat_off, js->v + first.flat_off, bytes,
-                               hipMemcpyDeviceToDevice, hs));
+    const int le = ps_launch_copy(js->p + first.flat_off, jd->p + first.flat_off, js->v + first.flat_off,
+                                  jd->v + first.flat_off, bytes / 4, stream);
+    if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
     a = z + 1;
   }
   Arrival* arr = arrival_get(dst);
