@@ -121,4 +121,8 @@ int ps_launch_wave(const PsWaveTables& t, void* stream);
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
                    void* stream);
 
+// Enqueue on stream the zeroing of n floats at p (16-byte aligned) with a fill
+// kernel (no memset node, so the call may sit inside a captured graph).
+int ps_launch_zero(float* p, uint64_t n, void* stream);
+
 #endif  // PS_INTERNAL_H_

@@ -348,6 +348,18 @@ __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict_
   }
 }
 
+// Zero n floats at p (16-byte aligned): a job's shards at registration.
+__global__ __launch_bounds__(PS_WG) void ps_zero_shards(float* __restrict__ p, unsigned long long n) {
+  constexpr int U = PS_TILE_QUADS_PER_LANE;
+  const unsigned long long at = (unsigned long long)blockIdx.x * PS_TILE_ELEMS;  // < n by the grid's size
+  const unsigned long long left = n - at;
+  const uint32_t bytes = (uint32_t)(left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
+  const __amdgpu_buffer_rsrc_t d = span(p + at, bytes);
+  const f32x4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int u = 0; u < U; ++u) store4(d, (u * PS_WG + threadIdx.x) * 16, z);
+}
+
 template <int W, bool FMA>
 void launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
                 uint32_t n_bins, uint32_t hold_ticks) {
@@ -410,6 +422,15 @@ int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* 
   if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
   hipLaunchKernelGGL(ps_copy_shards, dim3((uint32_t)tiles), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_),
                      src_p, dst_p, src_v, dst_v, (unsigned long long)n);
+  return (int)hipGetLastError();
+}
+
+int ps_launch_zero(float* p, uint64_t n, void* stream_) {
+  if (n == 0) return 0;
+  const uint64_t tiles = (n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
+  if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(ps_zero_shards, dim3((uint32_t)tiles), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_), p,
+                     (unsigned long long)n);
   return (int)hipGetLastError();
 }
 

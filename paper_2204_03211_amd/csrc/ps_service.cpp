@@ -547,7 +547,8 @@ static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_lay
     j.v = j.p + j.flat_numel;
     PS_HIP(c, hipHostMalloc((void**)&j.stat, nb * sizeof(double), hipHostMallocDefault));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemsetAsync(j.p, 0, j.arena_bytes, s);  // parameters' padding and all momentum
+    // parameters' padding and all momentum start at zero
+    hipError_t e = (hipError_t)ps_launch_zero(j.p, j.arena_bytes / 4, stream);
     if (e == hipSuccess && init_params) {
       int64_t flat = 0;
       for (int32_t l = 0; l < n_layers && e == hipSuccess; ++l) {
