@@ -112,8 +112,9 @@ struct PsWaveTables {
 uint32_t ps_resident_workgroups(uint32_t W);
 
 // Enqueue the kernels of one wave on stream (a hipStream_t).  Returns a
-// hipError_t value (0 = success).
-int ps_launch_wave(const PsWaveTables& t, void* stream);
+// hipError_t value (0 = success); stops at the first launch the runtime
+// refuses.  *launched = kernels enqueued before that.
+int ps_launch_wave(const PsWaveTables& t, void* stream, uint32_t* launched);
 
 // Enqueue on stream the copy of n floats of parameters and n floats of momentum
 // (both pairs 16-byte aligned) from one context's shards to another's: the

@@ -361,33 +361,40 @@ __global__ __launch_bounds__(PS_WG) void ps_zero_shards(float* __restrict__ p, u
 }
 
 template <int W, bool FMA>
-void launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
-                uint32_t n_bins, uint32_t hold_ticks) {
+hipError_t launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
+                      uint32_t n_bins, uint32_t hold_ticks) {
   hipLaunchKernelGGL((ps_agg_wave<W, FMA>), dim3(n_tiles + n_bins), dim3(PS_WG), 0, stream, t.recs,
                      t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins, hold_ticks);
+  return hipGetLastError();
 }
 
+// Returns the first launch error; *launched counts the launches that went in before it.
 template <bool FMA>
-void launch_agg(const PsWaveTables& t, hipStream_t stream) {
+hipError_t launch_agg(const PsWaveTables& t, hipStream_t stream, uint32_t* launched) {
   uint32_t bins_left = t.n_bins;
   if (t.n_chunks == 0 && bins_left) {
-    launch_one<0, FMA>(t, stream, 0, 0, bins_left, 0);
-    return;
+    const hipError_t e = launch_one<0, FMA>(t, stream, 0, 0, bins_left, 0);
+    if (e == hipSuccess) *launched += 1;
+    return e;
   }
   for (uint32_t c = 0; c < t.n_chunks; ++c) {
     const PsChunk& ch = t.chunks[c];
     const uint32_t nt = ch.end - ch.begin;
+    hipError_t e;
     // the bins ride with the first launch so that they overlap with tile work
     switch (ch.W) {
-      case 1: launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 2: launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 4: launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 8: launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 16: launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      default: launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 1: e = launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 2: e = launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 4: e = launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 8: e = launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 16: e = launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      default: e = launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
     }
+    if (e != hipSuccess) return e;
+    *launched += 1;
     bins_left = 0;
   }
+  return hipSuccess;
 }
 
 }  // namespace
@@ -434,19 +441,25 @@ int ps_launch_zero(float* p, uint64_t n, void* stream_) {
   return (int)hipGetLastError();
 }
 
-int ps_launch_wave(const PsWaveTables& t, void* stream_) {
+int ps_launch_wave(const PsWaveTables& t, void* stream_, uint32_t* launched) {
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   auto mark = [&](int i) {
     if (t.ev[i]) (void)hipEventRecord(static_cast<hipEvent_t>(t.ev[i]), stream);
   };
+  *launched = 0;
+  (void)hipGetLastError();  // an error left behind by an earlier, unrelated call is not this wave's
   mark(0);
-  if (t.fp_contract) launch_agg<true>(t, stream); else launch_agg<false>(t, stream);
+  hipError_t e = t.fp_contract ? launch_agg<true>(t, stream, launched) : launch_agg<false>(t, stream, launched);
+  if (e != hipSuccess) return (int)e;
   mark(1);
   if (t.n_large_blocks) {
     const uint32_t per = PS_WG / 64;
     hipLaunchKernelGGL(ps_block_norms, dim3((t.n_large_blocks + per - 1) / per), dim3(PS_WG), 0,
                        stream, t.recs, t.large_recs, t.n_large_blocks, t.tile_part);
+    e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    *launched += 1;
   }
   mark(2);
-  return (int)hipGetLastError();
+  return 0;
 }

@@ -992,9 +992,24 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   PsWaveTables t = s.tables;
   for (int i = 0; i < 3; ++i) t.ev[i] = ts ? ts->ev[i + 1] : nullptr;
   if (ts && !ts->all_phases) t.ev[2] = nullptr;
-  const int le = ps_launch_wave(t, stream);
+  uint32_t launched = 0;
+  const int le = ps_launch_wave(t, stream, &launched);
   if (le != 0) {
     s.valid = false;
+    if (launched > 0) {
+      // Part of the wave is enqueued and will update its blocks: the pushes are
+      // spent (a retry must not apply them again) and the wave cannot be taken
+      // back.  Which blocks were reached is not known to the caller.
+      for (int64_t i = 0; i < n; ++i) {
+        Block& b = c->jobs[list[i].job].blocks[list[i].block];
+        b.mask = 0;
+        b.round += 1;
+      }
+      (void)hip_fail(c, (hipError_t)le, "launching the wave");
+      c->last_error += " (after part of the wave was enqueued: its pushes are consumed, "
+                       "the listed blocks' contents are undefined)";
+      return PS_ERR_HIP;
+    }
     return hip_fail(c, (hipError_t)le, "launching the wave");
   }
   PS_HIP(c, hipEventRecord(s.done, hs));
