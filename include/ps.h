@@ -272,6 +272,27 @@ int32_t ps_estimate_wave(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n,
  * different streams that touch the same block must be ordered by the caller. */
 int32_t ps_aggregate(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, void* stream);
 
+/* ps_aggregate for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * validation, same kernels and same results as ps_aggregate, but the call
+ * allocates nothing on the device or through HIP (no hipMalloc, hipFree,
+ * hipHostMalloc, no event or stream creation): the wave's tables and the
+ * per-tile telemetry partials go into a device array of fixed size that is
+ * part of the library image (8 MiB per GPU, held until the process ends),
+ * through a pinned staging buffer that ps_create allocated.  A wave whose tables
+ * do not fit (16 bytes per tile of 4096 values plus 64 + 8 W bytes per block:
+ * about 2 G parameters in one wave, or some 25 000 blocks of 32 workers) is
+ * refused with PS_ERR_CAPACITY and nothing is launched or consumed;
+ * ps_last_error says how many bytes it needed.  Every use of the array on one
+ * GPU -- from any context, thread or stream -- is serialised: a call holds a
+ * per-GPU lock while it runs on the host, and its device work is ordered after
+ * the previous use of the array by an event.  Tables are re-used when the list
+ * and the pushed pointers repeat and no other call has used the array since;
+ * otherwise the call first waits on the host for the previous use to finish
+ * (the staging buffer is about to be rewritten).  Event timing
+ * (ps_timing_enable) does not cover these waves.  Other errors as ps_aggregate. */
+int32_t ps_aggregate_noalloc(ps_ctx* ctx, const ps_block_ref* block_list, int64_t n, void* stream);
+
 /* --- pull (service -> worker) and inspection ------------------------------- */
 
 /* The paper's Pull (Section 2: workers fetch the updated parameters before the

@@ -72,7 +72,7 @@ EXPORTS = [
     "ps_unregister_job", "ps_split_ready", "ps_migrate_begin", "ps_migrate_cancel", "ps_migrate_copy",
     "ps_migrate_many", "ps_estimate_wave",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
-    "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_pull", "ps_pull_momentum", "ps_pull_flat", "ps_pull_copy",
+    "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_aggregate_noalloc", "ps_pull", "ps_pull_momentum", "ps_pull_flat", "ps_pull_copy",
     "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
 ]
 
@@ -114,6 +114,7 @@ def load_library() -> C.CDLL:
     L.ps_plan_wave.argtypes = [vp, P(BlockRef), i64, P(WaveStats)]
     L.ps_estimate_wave.argtypes = [vp, P(BlockRef), i64, P(WaveStats)]
     L.ps_aggregate.argtypes = [vp, P(BlockRef), i64, vp]
+    L.ps_aggregate_noalloc.argtypes = [vp, P(BlockRef), i64, vp]
     L.ps_pull.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_momentum.argtypes = [vp, i32, i32, P(vp), P(i64)]
     L.ps_pull_flat.argtypes = [vp, i32, P(vp), P(vp), P(i64)]
@@ -180,7 +181,7 @@ class ParameterService:
     def _check(self, status: int) -> int:
         if status < 0:
             text = self.L.ps_strerror(status).decode()
-            if status == -11 and self.ctx:
+            if status in (-11, -12) and self.ctx:
                 text += " (" + self.L.ps_last_error(self.ctx).decode() + ")"
             raise PsError(status, text)
         return status
@@ -309,6 +310,10 @@ class ParameterService:
     def aggregate(self, wave: WaveList, stream: Optional[torch.cuda.Stream] = None) -> None:
         sp = _stream_ptr(stream) if self.arena is not None else None
         self._check(self.L.ps_aggregate(self.ctx, wave.arr, wave.n, sp))
+
+    def aggregate_noalloc(self, wave: WaveList, stream: Optional[torch.cuda.Stream] = None) -> None:
+        sp = _stream_ptr(stream) if self.arena is not None else None
+        self._check(self.L.ps_aggregate_noalloc(self.ctx, wave.arr, wave.n, sp))
 
     def pull(self, job: int, block: int) -> torch.Tensor:
         """The block's parameters as a view into the arena (no copy)."""

@@ -3,6 +3,7 @@
 #ifndef PS_INTERNAL_H_
 #define PS_INTERNAL_H_
 
+#include <stddef.h>
 #include <stdint.h>
 
 // One block of one job as the kernels see it: a 64-byte header followed
@@ -125,5 +126,28 @@ int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* 
 // Enqueue on stream the zeroing of n floats at p (16-byte aligned) with a fill
 // kernel (no memset node, so the call may sit inside a captured graph).
 int ps_launch_zero(float* p, uint64_t n, void* stream);
+
+// ---------------------------------------------------------------------------
+// Scratch memory that exists without any allocation: one file-scope device
+// array per GPU, for callers that may not allocate (ps_aggregate_noalloc).  It
+// holds what a slot's device buffer holds: the wave's tables and the tile
+// partials.  Every use on a GPU, from whatever context or stream, is ordered
+// after the previous use through `last` (an event created at set-up).
+// ---------------------------------------------------------------------------
+constexpr size_t PS_STATIC_SCRATCH_BYTES = 8u << 20;
+struct PsStaticScratch {
+  void* ptr;          // device address of this GPU's copy of the array
+  void* last;         // hipEvent_t recorded after the most recent use
+  void* last_stream;  // stream of that use
+  bool in_flight;     // `last` has been recorded at least once
+  uint64_t generation;  // bumped whenever new tables are copied into the array
+  void* use_mutex;    // std::mutex held for the length of one call that uses the array
+};
+// The scratch of the current device, set up on first use per device (address
+// looked up with the device current, event created).  Returns a hipError_t
+// value (0 = success).  Guard every use with ps_static_scratch_lock/unlock.
+int ps_static_scratch(PsStaticScratch** out);
+void ps_static_scratch_lock(PsStaticScratch* s);
+void ps_static_scratch_unlock(PsStaticScratch* s);
 
 #endif  // PS_INTERNAL_H_

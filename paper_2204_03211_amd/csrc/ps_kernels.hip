@@ -13,6 +13,8 @@
 // for this translation unit regardless of the command line.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "ps_internal.h"
 
 #pragma clang fp contract(off)
@@ -420,6 +422,59 @@ uint32_t ps_resident_workgroups(uint32_t W) {
     case 16: return resident_of<16>(cus);
     default: return resident_of<0>(cus);
   }
+}
+
+// ---------------------------------------------------------------------------
+// Static scratch.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device, with
+// that device current, and everything else uses that address.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticScratchSlot {
+  PsStaticScratch pub{};
+  std::mutex use;      // held for the length of one call that uses the array
+  bool ready = false;
+};
+StaticScratchSlot g_static[kMaxDevices];
+std::mutex g_static_setup;
+}  // namespace
+
+int ps_static_scratch(PsStaticScratch** out) {
+  *out = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return (int)e;
+  if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> g(g_static_setup);
+  StaticScratchSlot& s = g_static[dev];
+  if (!s.ready) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return (int)e;
+    if (!ptr) return (int)hipErrorInvalidSymbol;
+    hipEvent_t ev = nullptr;
+    e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+    if (e != hipSuccess) return (int)e;
+    s.pub.ptr = ptr;
+    s.pub.last = ev;
+    s.pub.last_stream = nullptr;
+    s.pub.in_flight = false;
+    s.pub.generation = 0;
+    s.pub.use_mutex = &s.use;
+    s.ready = true;
+  }
+  *out = &s.pub;
+  return 0;
+}
+
+void ps_static_scratch_lock(PsStaticScratch* s) {
+  static_cast<std::mutex*>(s->use_mutex)->lock();
+}
+void ps_static_scratch_unlock(PsStaticScratch* s) {
+  static_cast<std::mutex*>(s->use_mutex)->unlock();
 }
 
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,

@@ -96,6 +96,7 @@ struct Slot {
   bool in_flight = false;
   hipStream_t stream = nullptr;  // stream of the wave that last used the slot
   bool valid = false;            // plan and device tables are in step
+  uint64_t generation = 0;       // static scratch only: its generation when these tables went in
   Plan plan;
   PsWaveTables tables{};
 };
@@ -113,6 +114,8 @@ struct ps_ctx {
   Slot slots[kSlots];
   int next_slot = 0;
   int last_slot = -1;            // slot of the most recent wave (candidate for reuse)
+  Slot static_slot;              // ps_aggregate_noalloc: pinned staging from ps_create, device side = the static array
+  PsStaticScratch* sscratch = nullptr;  // this GPU's static array (looked up in ps_create)
   TimingSet tsets[kTimingSets];
   int next_tset = 0;
   Plan plan;                     // scratch of ps_plan_wave
@@ -419,6 +422,58 @@ size_t place(size_t* cursor, size_t count) {
   return at;
 }
 
+// Where the tables of a plan sit inside a slot's buffer.
+struct Offsets {
+  size_t recs, tiles, small, bins, large, upload, part, total;
+};
+
+Offsets offsets_of(const Plan& P) {
+  Offsets o{};
+  size_t cur = 0;
+  o.recs = place<unsigned char>(&cur, P.recs.size());
+  o.tiles = place<PsTile>(&cur, P.tiles.size());
+  o.small = place<PsSmallEntry>(&cur, P.small_entries.size());
+  o.bins = place<PsBin>(&cur, P.bins.size());
+  o.large = place<uint32_t>(&cur, P.large_recs.size());
+  o.upload = cur;
+  o.part = place<double>(&cur, P.tiles.size());
+  o.total = cur;
+  return o;
+}
+
+void stage_tables(const Plan& P, const Offsets& o, char* host) {
+  auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(host + at, src, bytes); };
+  put(o.recs, P.recs.data(), P.recs.size());
+  put(o.tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
+  put(o.small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
+  put(o.bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
+  put(o.large, P.large_recs.data(), P.large_recs.size() * sizeof(uint32_t));
+}
+
+void bind_tables(const ps_ctx* c, Slot& s, const Offsets& o, char* dev) {
+  const Plan& P = s.plan;
+  PsWaveTables& t = s.tables;
+  t = PsWaveTables{};
+  t.recs = reinterpret_cast<const unsigned char*>(dev + o.recs);
+  t.tiles = reinterpret_cast<const PsTile*>(dev + o.tiles);
+  t.n_tiles = (uint32_t)P.tiles.size();
+  t.chunks = P.chunks.data();
+  t.n_chunks = (uint32_t)P.chunks.size();
+  t.tile_part = reinterpret_cast<double*>(dev + o.part);
+  t.small_entries = reinterpret_cast<const PsSmallEntry*>(dev + o.small);
+  t.bins = reinterpret_cast<const PsBin*>(dev + o.bins);
+  t.n_bins = (uint32_t)P.bins.size();
+  t.large_recs = reinterpret_cast<const uint32_t*>(dev + o.large);
+  t.n_large_blocks = (uint32_t)P.large_recs.size();
+  t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
+}
+
+struct ScratchGuard {
+  PsStaticScratch* s;
+  explicit ScratchGuard(PsStaticScratch* x) : s(x) { if (s) ps_static_scratch_lock(s); }
+  ~ScratchGuard() { if (s) ps_static_scratch_unlock(s); }
+};
+
 }  // namespace
 
 // No C++ exception leaves the library.  What this code can raise are failed
@@ -468,6 +523,14 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) try {
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
       c->clock_hz = 1000.0 * khz;
     for (uint32_t w = 0; w <= PS_MAX_W; ++w) c->resident_tiles[w] = ps_resident_workgroups(w);
+    // everything ps_aggregate_noalloc will need, so that it never allocates:
+    // this GPU's static array and a pinned staging buffer of the same size
+    if (ps_static_scratch(&c->sscratch) != 0 ||
+        hipHostMalloc((void**)&c->static_slot.host, PS_STATIC_SCRATCH_BYTES, hipHostMallocDefault) != hipSuccess) {
+      delete c;
+      return PS_ERR_HIP;
+    }
+    c->static_slot.host_cap = PS_STATIC_SCRATCH_BYTES;
   }
   *out_ctx = c;
   return PS_OK;
@@ -482,6 +545,7 @@ void ps_destroy(ps_ctx* c) {
     if (s.host) (void)hipHostFree(s.host);
     if (s.dev) (void)hipFree(s.dev);
   }
+  if (c->static_slot.host) (void)hipHostFree(c->static_slot.host);
   for (TimingSet& t : c->tsets)
     for (hipEvent_t e : t.ev)
       if (e) (void)hipEventDestroy(e);
@@ -901,7 +965,10 @@ int32_t ps_estimate_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave
   return PS_OK;
 } PS_NO_THROW
 
-int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) try {
+// The body of ps_aggregate and ps_aggregate_noalloc.  noalloc: the tables go
+// into this GPU's static array through the staging buffer of ps_create instead
+// of a slot that grows on demand, and no event is created.
+static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream, bool noalloc) {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
   int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
@@ -909,6 +976,9 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   if (n == 0) return PS_OK;
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
   hipStream_t hs = static_cast<hipStream_t>(stream);
+  PsStaticScratch* ss = noalloc ? c->sscratch : nullptr;
+  if (noalloc && !ss) return PS_ERR_NO_DEVICE;
+  ScratchGuard scratch_guard(ss);
 
   // A shard that arrived by migration must not be updated before its copy is
   // complete (the new owner's consistency rule): order this stream after it.
@@ -927,7 +997,14 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
   // if the previous wave's tables still describe this one, use them as they are.
   Slot* sp = nullptr;
   bool reuse = false;
-  if (c->last_slot >= 0) {
+  if (noalloc) {
+    Slot& ls = c->static_slot;
+    sp = &ls;
+    reuse = ls.valid && ls.generation == ss->generation && ls.plan.sig == c->sig;
+    // the array (tables and tile partials) is shared with whatever used it last
+    if (reuse && ss->in_flight && ss->last_stream != stream)
+      PS_HIP(c, hipStreamWaitEvent(hs, static_cast<hipEvent_t>(ss->last), 0));
+  } else if (c->last_slot >= 0) {
     Slot& ls = c->slots[c->last_slot];
     if (ls.valid && ls.plan.sig == c->sig) {
       sp = &ls;
@@ -937,7 +1014,7 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     }
   }
   TimingSet* ts = nullptr;
-  if (c->timing_level > 0) {
+  if (c->timing_level > 0 && !noalloc) {
     ts = &c->tsets[c->next_tset];
     c->next_tset = (c->next_tset + 1) % kTimingSets;
     st = timing_harvest(c, *ts);
@@ -947,46 +1024,37 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     ts->all_phases = c->timing_level >= 2;
     if (ts->all_phases) PS_HIP(c, hipEventRecord(ts->ev[0], hs));
   }
-  if (!reuse) {
+  if (!reuse && noalloc) {
+    Slot& s = *sp;
+    s.valid = false;
+    layout_plan(c, list, n, s.plan);
+    const Offsets o = offsets_of(s.plan);
+    if (o.total > PS_STATIC_SCRATCH_BYTES) {
+      c->last_error = "ps_aggregate_noalloc: the wave's tables need " + std::to_string(o.total) +
+                      " bytes of scratch, the static array holds " + std::to_string(PS_STATIC_SCRATCH_BYTES);
+      return PS_ERR_CAPACITY;
+    }
+    // the staging buffer and the array may still be in use by the previous call
+    if (ss->in_flight) PS_HIP(c, hipEventSynchronize(static_cast<hipEvent_t>(ss->last)));
+    stage_tables(s.plan, o, s.host);
+    ss->generation += 1;   // whatever happens next, older tables are gone
+    PS_HIP(c, hipMemcpyAsync(ss->ptr, s.host, o.upload, hipMemcpyHostToDevice, hs));
+    bind_tables(c, s, o, static_cast<char*>(ss->ptr));
+    s.generation = ss->generation;
+    s.plan.sig = c->sig;
+  } else if (!reuse) {
     c->next_slot = (c->last_slot + 1) % kSlots;
     sp = &c->slots[c->next_slot];
     Slot& s = *sp;
     s.valid = false;
-    Plan& P = s.plan;
-    layout_plan(c, list, n, P);
-    size_t cur = 0;
-    const size_t o_recs = place<unsigned char>(&cur, P.recs.size());
-    const size_t o_tiles = place<PsTile>(&cur, P.tiles.size());
-    const size_t o_small = place<PsSmallEntry>(&cur, P.small_entries.size());
-    const size_t o_bins = place<PsBin>(&cur, P.bins.size());
-    const size_t o_large = place<uint32_t>(&cur, P.large_recs.size());
-    const size_t upload = cur;
-    const size_t o_part = place<double>(&cur, P.tiles.size());
-    const size_t dev_total = cur;
-    st = slot_reserve(c, s, upload, dev_total);
+    layout_plan(c, list, n, s.plan);
+    const Offsets o = offsets_of(s.plan);
+    st = slot_reserve(c, s, o.upload, o.total);
     if (st != PS_OK) return st;
-    auto put = [&](size_t at, const void* src, size_t bytes) { if (bytes) std::memcpy(s.host + at, src, bytes); };
-    put(o_recs, P.recs.data(), P.recs.size());
-    put(o_tiles, P.tiles.data(), P.tiles.size() * sizeof(PsTile));
-    put(o_small, P.small_entries.data(), P.small_entries.size() * sizeof(PsSmallEntry));
-    put(o_bins, P.bins.data(), P.bins.size() * sizeof(PsBin));
-    put(o_large, P.large_recs.data(), P.large_recs.size() * sizeof(uint32_t));
-    PS_HIP(c, hipMemcpyAsync(s.dev, s.host, upload, hipMemcpyHostToDevice, hs));
-    PsWaveTables& t = s.tables;
-    t = PsWaveTables{};
-    t.recs = reinterpret_cast<const unsigned char*>(s.dev + o_recs);
-    t.tiles = reinterpret_cast<const PsTile*>(s.dev + o_tiles);
-    t.n_tiles = (uint32_t)P.tiles.size();
-    t.chunks = P.chunks.data();
-    t.n_chunks = (uint32_t)P.chunks.size();
-    t.tile_part = reinterpret_cast<double*>(s.dev + o_part);
-    t.small_entries = reinterpret_cast<const PsSmallEntry*>(s.dev + o_small);
-    t.bins = reinterpret_cast<const PsBin*>(s.dev + o_bins);
-    t.n_bins = (uint32_t)P.bins.size();
-    t.large_recs = reinterpret_cast<const uint32_t*>(s.dev + o_large);
-    t.n_large_blocks = (uint32_t)P.large_recs.size();
-    t.fp_contract = (c->cfg.flags & PS_FLAG_FP_CONTRACT) != 0;
-    P.sig = c->sig;
+    stage_tables(s.plan, o, s.host);
+    PS_HIP(c, hipMemcpyAsync(s.dev, s.host, o.upload, hipMemcpyHostToDevice, hs));
+    bind_tables(c, s, o, s.dev);
+    s.plan.sig = c->sig;
   }
   Slot& s = *sp;
   PsWaveTables t = s.tables;
@@ -1012,11 +1080,17 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     }
     return hip_fail(c, (hipError_t)le, "launching the wave");
   }
-  PS_HIP(c, hipEventRecord(s.done, hs));
-  s.in_flight = true;
-  s.stream = hs;
+  if (noalloc) {
+    PS_HIP(c, hipEventRecord(static_cast<hipEvent_t>(ss->last), hs));
+    ss->in_flight = true;
+    ss->last_stream = stream;
+  } else {
+    PS_HIP(c, hipEventRecord(s.done, hs));
+    s.in_flight = true;
+    s.stream = hs;
+    c->last_slot = (int)(sp - c->slots);
+  }
   s.valid = true;
-  c->last_slot = (int)(sp - c->slots);
   if (ts) {
     ts->pending = true;
     ts->launches = s.plan.stats.n_launches;
@@ -1031,6 +1105,14 @@ int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* strea
     j.stat_round[list[i].block] = b.round;
   }
   return PS_OK;
+}
+
+int32_t ps_aggregate(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) try {
+  return aggregate_impl(c, list, n, stream, /*noalloc=*/false);
+} PS_NO_THROW
+
+int32_t ps_aggregate_noalloc(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream) try {
+  return aggregate_impl(c, list, n, stream, /*noalloc=*/true);
 } PS_NO_THROW
 
 int32_t ps_pull(ps_ctx* c, ps_job_t job, int32_t block, const float** out_param_dev, int64_t* out_numel) try {

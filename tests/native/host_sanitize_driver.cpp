@@ -14,6 +14,9 @@
 #include "../../paper_2204_03211_amd/csrc/ps_internal.h"
 
 int ps_launch_wave(const PsWaveTables&, void*, uint32_t* launched) { *launched = 0; return 0; }
+int ps_static_scratch(PsStaticScratch** out) { *out = nullptr; return 1; }
+void ps_static_scratch_lock(PsStaticScratch*) {}
+void ps_static_scratch_unlock(PsStaticScratch*) {}
 int ps_launch_zero(float*, uint64_t, void*) { return 0; }
 int ps_launch_copy(const float*, float*, const float*, float*, uint64_t, void*) { return 0; }
 uint32_t ps_resident_workgroups(uint32_t) { return 2048; }
