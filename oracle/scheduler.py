@@ -25,7 +25,19 @@ Readings where the printed pseudocode is garbled or silent:
   * loss is compared with >= LossLimit, as printed;
   * "least-loaded" Aggregator on recycling = smallest busy time per cycle
     divided by the cycle (ties to the highest id, so that younger Aggregators go
-    first).
+    first);
+  * scaling up on arrival (Section 3.3.2: add an Aggregator, assign the entire
+    job again, repeat until the job no longer loses speed): the job was placed
+    where the estimates said it would not lose speed and lost speed all the
+    same, so running the same estimates again over one more (empty) Aggregator
+    would put every task back where it was -- best fit never prefers the
+    emptiest destination.  The reading taken: the Aggregators added for this
+    job by scale-up steps are offered FIRST, oldest first, each to every task
+    it still qualifies for (loss test, F >= e_t); only a task that none of them
+    holds goes through Pseudocode 1 over the other Aggregators.  Every step
+    then takes up to one cycle's worth of the job's aggregations off the
+    shared Aggregators, and the loop ends at the latest when the job sits on
+    Aggregators of its own, which is its standalone placement.
 """
 from __future__ import annotations
 
@@ -64,6 +76,7 @@ class SchedulerOracle:
         self.D: Dict[int, float] = {}
         self.aggs: Dict[int, Aggregator] = {}
         self.where: Dict[int, Tuple[int, int, float]] = {}   # task id -> (aggregator, job, e_t)
+        self.own: Dict[int, List[int]] = {}   # job -> Aggregators added for it by scale-up, oldest first
         self.next_agg = 0
         self.next_task = 0
         self.next_job = 0
@@ -118,6 +131,14 @@ class SchedulerOracle:
         self.next_agg += 1
         self.aggs[n] = Aggregator(n)
         return n
+
+    def _release(self, n: int) -> None:
+        """Hand an (empty) Aggregator back; no job keeps it as one of its own."""
+        del self.aggs[n]
+        for k in list(self.own):
+            self.own[k] = [m for m in self.own[k] if m != n]
+            if not self.own[k]:
+                del self.own[k]
 
     def _place(self, n: int, k: int, e: float, task: Optional[int] = None) -> int:
         if task is None:
@@ -182,16 +203,17 @@ class SchedulerOracle:
             for t, _ in a.tasks.pop(k, []):
                 del self.where[t]
         del self.D[k]
+        self.own.pop(k, None)
         for n in sorted(self.aggs):
             if self.aggs[n].empty():
-                del self.aggs[n]
+                self._release(n)
                 released.append(n)
         while len(self.aggs) > 1:
             victim = min(self.aggs, key=lambda n: (self.busy(n) / self.cycle(n), -n))
             moved = self._drain(victim)
             if not moved:
                 break
-            del self.aggs[victim]
+            self._release(victim)
             released.append(victim)
         return released
 
@@ -215,30 +237,128 @@ class SchedulerOracle:
         return True
 
     # -- scaling on job arrival (Section 3.3.2) ---------------------------------
-    def scale_up_job(self, k: int) -> int:
+    def scale_up_job(self, k: int) -> Tuple[int, int]:
         """The monitored job k runs slower than standalone: allocate one more
-        Aggregator and assign the whole job again, task by task in task-id order,
-        with the new (empty) Aggregator among the destinations.  The caller
-        repeats this while the measured loss stays above LossLimit.  Returns the
-        new Aggregator's id; Aggregators that end up empty are released."""
+        Aggregator for it and assign the whole job again, task by task in task-id
+        order.  The Aggregators added for k (by earlier calls and by this one) are
+        offered first, oldest first: a task goes to the first of them that passes
+        the loss test and has F >= e_t; a task that none of them holds goes through
+        Pseudocode 1 over the other Aggregators.  Aggregators left empty are
+        released.  Returns (the new Aggregator's id, the number of k's tasks whose
+        Aggregator changed); the caller repeats while the measured loss stays above
+        LossLimit and the second number is not zero."""
         mine = sorted((t, e) for t, (n, j, e) in self.where.items() if j == k)
+        before = {t: self.where[t][0] for t, _ in mine}
         for t, e in mine:
             n = self.where[t][0]
             self.aggs[n].tasks[k].remove((t, e))
             if not self.aggs[n].tasks[k]:
                 del self.aggs[n].tasks[k]
         fresh = self.allocate()
+        self.own.setdefault(k, []).append(fresh)
         for t, e in mine:
-            n = self.choose(k, e)
+            n = None
+            for cand in self.own[k]:
+                est = self.estimate(cand, k)
+                if est is not None and est[1] >= e:
+                    n = cand
+                    break
+            if n is None:
+                n = self.choose(k, e, exclude=tuple(self.own[k]))
             self._place(n, k, e, task=t)
         for n in sorted(self.aggs):
             if self.aggs[n].empty():
-                del self.aggs[n]
-        return fresh
+                self._release(n)
+        moved = sum(1 for t, _ in mine if self.where[t][0] != before[t])
+        return fresh, moved
 
     # -- two-level placement (Section 3.3.3) ------------------------------------
     @staticmethod
     def best_fit_cluster(free: List[float], demand: float) -> Optional[int]:
-        """The cluster with sufficient but the least free time; None if none fits."""
+        """The cluster with sufficient but the least free resource; None if none fits."""
         ok = [(f, i) for i, f in enumerate(free) if f >= demand]
         return min(ok)[1] if ok else None
+
+
+class PMasterOracle:
+    """Aggregator clusters (Section 3.3.3).  The pool of Aggregators is split
+    into independent clusters; each has a controller that runs the assignment
+    scheme over its own Aggregators only (one SchedulerOracle per cluster, with
+    Aggregator and task ids local to the cluster).  pMaster keeps, on its own
+    side, the remaining free resource of every cluster and places a new job in
+    two steps: it forwards the job to the best-fit cluster by the job's total
+    demand, then that cluster's controller assigns the job's model aggregations;
+    a job takes resource from one cluster only.  When a job exits, its
+    controller reports it and pMaster gives the job's demand back to the cluster.
+
+    Readings where the text is silent:
+      * unit of "CPU resource": Aggregators.  A cluster of capacity M offers M
+        units; a job with profiled duration D and tasks e_t consumes
+        sum(e_t) / D of one Aggregator (its aggregation time per unit of time);
+        free = capacity - sum of the demands of the jobs forwarded there.  This
+        is pMaster's own book, kept from profiled job information: it does not
+        look at how the controller packed the tasks;
+      * ties between equally free clusters go to the lowest cluster id;
+      * if no cluster has room the job is not placed (None): adding clusters or
+        Aggregators to a cluster is the periodic scaling policy, not part of
+        this step;
+      * scaling a job up happens inside its cluster and leaves its demand, and
+        therefore pMaster's book, unchanged.
+    """
+
+    def __init__(self, loss_limit: float = LOSS_LIMIT_DEFAULT):
+        self.loss_limit = loss_limit
+        self.capacity: List[float] = []
+        self.controllers: List[SchedulerOracle] = []
+        self.jobs: Dict[int, Tuple[int, int, float]] = {}   # job -> (cluster, controller's job id, demand)
+        self.next_job = 0
+
+    def add_cluster(self, capacity: float) -> int:
+        assert capacity > 0
+        self.capacity.append(capacity)
+        self.controllers.append(SchedulerOracle(self.loss_limit))
+        return len(self.capacity) - 1
+
+    def used(self, c: int) -> float:
+        total = 0.0
+        for j in sorted(self.jobs):
+            if self.jobs[j][0] == c:
+                total += self.jobs[j][2]
+        return total
+
+    def free(self, c: int) -> float:
+        return self.capacity[c] - self.used(c)
+
+    @staticmethod
+    def demand(D: float, es: List[float]) -> float:
+        total = 0.0
+        for e in es:
+            total += e
+        return total / D
+
+    def forward_job(self, D: float, es: List[float]) -> Optional[Tuple[int, int, List[Tuple[int, int]]]]:
+        """A new job with profiled iteration D and task execution times es.
+        -> (job id, cluster, [(task id, Aggregator)] in the cluster's own ids), or
+        None if no cluster has room for its demand."""
+        need = self.demand(D, es)
+        c = SchedulerOracle.best_fit_cluster([self.free(i) for i in range(len(self.capacity))], need)
+        if c is None:
+            return None
+        ctl = self.controllers[c]
+        local = ctl.add_job(D)
+        placed = [ctl.assign(local, e) for e in es]
+        j = self.next_job
+        self.next_job += 1
+        self.jobs[j] = (c, local, need)
+        return j, c, placed
+
+    def job_exit(self, j: int) -> Tuple[int, List[int]]:
+        """The controller removes the job (releasing and recycling Aggregators
+        inside its cluster) and reports the exit; pMaster forgets the job, which
+        gives its demand back.  -> (cluster, Aggregators released there)."""
+        c, local, _ = self.jobs.pop(j)
+        return c, self.controllers[c].remove_job(local)
+
+    def scale_up_job(self, j: int) -> Tuple[int, int]:
+        c, local, _ = self.jobs[j]
+        return self.controllers[c].scale_up_job(local)

@@ -7,7 +7,7 @@ from fractions import Fraction as Fr
 import numpy as np
 import pytest
 
-from oracle.scheduler import LOSS_LIMIT_DEFAULT, SchedulerOracle, iteration_duration, loss
+from oracle.scheduler import LOSS_LIMIT_DEFAULT, PMasterOracle, SchedulerOracle, iteration_duration, loss
 
 
 def test_default_loss_limit():
@@ -188,9 +188,12 @@ def test_best_fit_cluster():
     assert f([3.0, 3.0], 3.0) == 0
 
 
-def test_scale_up_gives_a_slow_job_room():
-    """Section 3.3.2: if a new job runs slower than alone, one more Aggregator is
-    added and the whole job is assigned again."""
+def test_scale_up_moves_a_job_off_a_full_aggregator():
+    """Section 3.3.2: a new job that runs slower than alone gets one more
+    Aggregator and is assigned again, until it no longer loses speed.  The job
+    sits on an Aggregator filled 10 of 10: after one step it must sit somewhere
+    else (plain best fit would put it straight back), and a further step, which
+    has nothing left to gain, must say so and hand its Aggregator back."""
     s = SchedulerOracle()
     a, b = s.add_job(10.0), s.add_job(10.0)
     for _ in range(3):
@@ -198,29 +201,146 @@ def test_scale_up_gives_a_slow_job_room():
     for _ in range(2):
         s.assign(b, 2.0)                       # 10 of 10 used on Aggregator 0: no slack at all
     assert sorted(s.aggs) == [0] and s.free(0) == 0.0
-    fresh = s.scale_up_job(b)
-    assert fresh == 1
-    # b's tasks are re-assigned by best fit: 0 has 4 free, 1 has 10: the first goes to 0 (tightest
-    # that fits), the second too (2 free >= 2)
-    assert sorted(n for n, j, e in s.where.values() if j == b) == [0, 0]
-    assert sorted(s.aggs) == [0]               # the unused new Aggregator is handed back
-    # a job too big for the slack does move
-    c = s.add_job(10.0)
-    s2 = SchedulerOracle()
-    x, y = s2.add_job(10.0), s2.add_job(10.0)
-    s2._place(s2.allocate(), x, 5.0)
-    s2._place(0, y, 3.0)
-    s2._place(0, y, 2.0)
-    s2.scale_up_job(y)                          # y off: 0 has 5 free; 3.0 -> 0 (5>=3), 2.0 -> 0 (2>=2)
-    assert all(n == 0 for n, j, e in s2.where.values())
-    s3 = SchedulerOracle()
-    x, y = s3.add_job(10.0), s3.add_job(10.0)
-    s3._place(s3.allocate(), x, 8.0)
-    s3._place(0, y, 1.5)
-    s3._place(0, y, 1.5)                         # over-full on purpose (11 of 10)
-    s3.scale_up_job(y)                           # 0 has 2 free: first 1.5 fits there, second (0.5 free) -> 1
-    assert sorted(n for n, j, e in s3.where.values() if j == y) == [0, 1]
-    assert sorted(s3.aggs) == [0, 1]
+    before = sorted(n for n, j, e in s.where.values() if j == b)
+    fresh, moved = s.scale_up_job(b)
+    after = sorted(n for n, j, e in s.where.values() if j == b)
+    assert (fresh, moved) == (1, 2) and before == [0, 0] and after == [1, 1]
+    assert sorted(s.aggs) == [0, 1] and s.free(0) == 4.0 and s.free(1) == 6.0
+    assert sorted(n for n, j, e in s.where.values() if j == a) == [0, 0, 0]   # nobody else moves
+    fresh, moved = s.scale_up_job(b)           # b already has an Aggregator to itself
+    assert (fresh, moved) == (2, 0)
+    assert sorted(s.aggs) == [0, 1]            # the unused new Aggregator is handed back
+    assert sorted(n for n, j, e in s.where.values() if j == b) == [1, 1]
+
+
+def test_scale_up_takes_one_aggregator_of_load_per_step():
+    """A job larger than one Aggregator: every step moves what one more
+    Aggregator holds; what is left over goes through the assignment scheme over
+    the others; the loop ends with the job on Aggregators of its own."""
+    s = SchedulerOracle()
+    x, y = s.add_job(10.0), s.add_job(10.0)
+    s.assign(x, 5.0)
+    ty = [s.assign(y, 4.0)[0] for _ in range(3)]
+    assert [s.where[t][0] for t in ty] == [0, 1, 1]       # 5 free on 0 takes one; the rest open 1
+    assert s.scale_up_job(y) == (2, 3)
+    # the new Aggregator takes two (8 of 10); the third goes by best fit: 0 (5 free) before the emptied 1 (10)
+    assert [s.where[t][0] for t in ty] == [2, 2, 0] and sorted(s.aggs) == [0, 2]
+    assert s.scale_up_job(y) == (3, 1)
+    assert [s.where[t][0] for t in ty] == [2, 2, 3] and sorted(s.aggs) == [0, 2, 3]
+    assert s.own[y] == [2, 3] and s.busy(0) == 5.0
+    assert s.scale_up_job(y) == (4, 0)
+    assert [s.where[t][0] for t in ty] == [2, 2, 3] and sorted(s.aggs) == [0, 2, 3] and s.own[y] == [2, 3]
+    # y leaves: its own Aggregators go back, nothing refers to them any more
+    assert s.remove_job(y) == [2, 3] and s.own == {}
+
+
+def test_scale_up_keeps_the_loss_test_on_the_jobs_own_aggregators():
+    s = SchedulerOracle()
+    k, f = s.add_job(12.0), s.add_job(5.0)
+    other = s.add_job(12.0)
+    s.assign(other, 9.0)
+    tk = s.assign(k, 2.0)[0]
+    assert s.where[tk][0] == 0
+    assert s.scale_up_job(k) == (1, 1) and s.where[tk][0] == 1 and s.own[k] == [1]
+    s._place(1, f, 0.5)                        # forced: f (iteration 5) would lose 17 % under cycle 12
+    assert s.estimate(1, k) is None
+    fresh, moved = s.scale_up_job(k)
+    assert (fresh, moved) == (2, 1) and s.where[tk][0] == 2     # 1 no longer qualifies, although it has room
+    assert s.own[k] == [1, 2] and sorted(s.aggs) == [0, 1, 2]
+
+
+def test_scale_up_loop_ends_with_the_job_on_its_own_aggregators():
+    rng = np.random.default_rng(5)
+    for trial in range(25):
+        s = SchedulerOracle()
+        jobs = [s.add_job(float(rng.choice([4, 5, 6, 8, 10, 12, 20, 24]))) for _ in range(5)]
+        tasks = {j: [] for j in jobs}
+        for _ in range(50):
+            j = jobs[int(rng.integers(len(jobs)))]
+            tasks[j].append(s.assign(j, float(rng.integers(1, 8)) / 8.0 * s.D[j] / 4.0)[0])
+        k = max(jobs, key=lambda j: len(tasks[j]))
+        others = {t: w for t, w in s.where.items() if w[1] != k}
+        shared_before = None
+        for step in range(len(tasks[k]) + 2):
+            fresh, moved = s.scale_up_job(k)
+            shared = sum(e for t, (n, j, e) in s.where.items() if j == k and n not in s.own.get(k, []))
+            assert shared_before is None or shared <= shared_before      # never back onto shared Aggregators
+            shared_before = shared
+            if moved == 0:
+                break
+        assert moved == 0 and step <= len(tasks[k])
+        assert all(s.where[t][0] in s.own[k] for t in tasks[k])
+        assert {t: w for t, w in s.where.items() if w[1] != k} == others  # the other jobs never move
+        assert all(not s.aggs[n].empty() for n in s.aggs)
+
+
+def test_pmaster_forwards_to_the_best_fit_cluster():
+    """Section 3.3.3: pMaster keeps each cluster's remaining free resource and
+    forwards a new job to the cluster with sufficient but least of it, by the
+    job's total demand; the controller there assigns every task inside that one
+    cluster; an exit is reported back and frees the room."""
+    m = PMasterOracle()
+    assert [m.add_cluster(c) for c in (2.0, 1.0, 3.0)] == [0, 1, 2]
+    assert PMasterOracle.demand(10.0, [2.0, 2.0, 1.0]) == 0.5
+    j0, c0, placed0 = m.forward_job(10.0, [2.0, 2.0, 1.0])            # demand 0.5: free 2, 1, 3 -> cluster 1
+    assert (j0, c0) == (0, 1) and placed0 == [(0, 0), (1, 0), (2, 0)]
+    assert [m.free(c) for c in range(3)] == [2.0, 0.5, 3.0]
+    j1, c1, placed1 = m.forward_job(10.0, [4.0, 4.0])                 # 0.8: 1 has 0.5 only -> 0 (2 before 3)
+    assert (j1, c1) == (1, 0) and placed1 == [(0, 0), (1, 0)]          # ids are the cluster's own
+    assert m.forward_job(5.0, [5.0, 5.0, 5.0, 2.0]) is None           # 3.4: nobody has that much
+    assert len(m.jobs) == 2 and m.next_job == 2                       # nothing was registered
+    j2, c2, _ = m.forward_job(4.0, [1.0, 1.0])                        # 0.5: cluster 1 has exactly 0.5
+    assert (j2, c2) == (2, 1) and m.free(1) == 0.0
+    j3, c3, _ = m.forward_job(4.0, [1.0])                             # 0.25: 0 has 1.2, 2 has 3 -> 0
+    assert c3 == 0 and m.free(0) == 2.0 - 0.8 - 0.25
+    # one job, one cluster: every controller only knows the tasks of its own jobs
+    assert sum(len(ctl.where) for ctl in m.controllers) == 3 + 2 + 2 + 1
+    assert len(m.controllers[1].where) == 5 and len(m.controllers[2].where) == 0
+    # exit: the controller recycles inside its cluster, pMaster's book gets the demand back
+    c, released = m.job_exit(j0)
+    assert c == 1 and m.free(1) == 0.5 and j0 not in m.jobs
+    assert released == [0] == lone_controller_release_after_exit()
+    j4, c4, _ = m.forward_job(10.0, [3.0])                            # 0.3 fits cluster 1 again (0.5 least)
+    assert c4 == 1
+    # ties between equally free clusters go to the lowest id
+    t = PMasterOracle()
+    t.add_cluster(1.0), t.add_cluster(1.0)
+    assert t.forward_job(10.0, [1.0])[1] == 0                         # 1.0 and 1.0 free: the first
+    assert t.forward_job(10.0, [1.0])[1] == 0                         # 0.9 and 1.0: still the tighter one
+    assert t.forward_job(10.0, [9.0])[1] == 1                         # 0.9 needed: only cluster 1 (1.0) has it
+
+
+def lone_controller_release_after_exit():
+    """The same exit on a lone controller: jobs (10: 2,2,1) and (4: 1,1) share
+    Aggregator 0?  No: under cycle 10 the second job (iteration 4) would run
+    twice at 5 and lose 20 %, so it sits on Aggregator 1; when the first job
+    leaves, Aggregator 0 is empty and released."""
+    s = SchedulerOracle()
+    a = s.add_job(10.0)
+    for e in (2.0, 2.0, 1.0):
+        s.assign(a, e)
+    b = s.add_job(4.0)
+    assert [s.assign(b, 1.0)[1] for _ in range(2)] == [1, 1]
+    return s.remove_job(a)
+
+
+def test_pmaster_book_is_demand_not_packing_and_scale_up_stays_inside():
+    m = PMasterOracle()
+    m.add_cluster(1.5), m.add_cluster(4.0)
+    ja, ca, _ = m.forward_job(10.0, [2.0, 2.0, 2.0])                  # 0.6 -> cluster 0 (1.5 < 4)
+    jb, cb, pb = m.forward_job(10.0, [2.0, 2.0])                      # 0.4 -> cluster 0 (0.9 left)
+    assert (ca, cb) == (0, 0) and m.free(0) == pytest.approx(0.5) and m.free(1) == 4.0
+    assert m.used(0) == 0.6 + 0.4
+    ctl = m.controllers[0]
+    assert sorted(ctl.aggs) == [0] and ctl.free(0) == 0.0             # packed onto one Aggregator, 10 of 10
+    fresh, moved = m.scale_up_job(jb)                                 # inside cluster 0, by the controller
+    assert (fresh, moved) == (1, 2) and sorted(ctl.aggs) == [0, 1]
+    assert m.free(0) == pytest.approx(0.5) and m.free(1) == 4.0       # pMaster's book did not move
+    assert len(m.controllers[1].aggs) == 0
+    jc, cc, _ = m.forward_job(10.0, [6.0])                            # 0.6 > 0.5: cluster 0 is full by the book
+    assert cc == 1
+    assert m.job_exit(ja) == (0, [0])                                 # ja alone on Aggregator 0: released
+    assert m.free(0) == pytest.approx(1.1)
 
 
 def _golden(name):

@@ -45,7 +45,7 @@ MUTANTS = {
         "return (C - elapsed) - remaining_scheduled >= e_late", "return C - remaining_scheduled >= e_late"),
     "exit does not recycle": ("        while len(self.aggs) > 1:\n", "        while False:\n"),
     "exit keeps empty Aggregators": (
-        "            if self.aggs[n].empty():\n                del self.aggs[n]\n                released.append(n)\n        while",
+        "            if self.aggs[n].empty():\n                self._release(n)\n                released.append(n)\n        while",
         "            pass\n        while"),
     "drains the most loaded": (
         "victim = min(self.aggs, key=lambda n: (self.busy(n) / self.cycle(n), -n))",
@@ -60,6 +60,29 @@ MUTANTS = {
     "failed drain not rolled back": ("                for t2, n2, j2, e2 in done:           # roll back\n",
                                      "                for t2, n2, j2, e2 in []:\n"),
     "scale-up adds nothing": ("        fresh = self.allocate()\n", "        fresh = max(self.aggs)\n"),
+    "scale-up runs plain best fit again": ("            for cand in self.own[k]:\n", "            for cand in []:\n"),
+    "scale-up offers the newest Aggregator first": (
+        "            for cand in self.own[k]:\n", "            for cand in reversed(self.own[k]):\n"),
+    "own Aggregators skip the room test": (
+        "if est is not None and est[1] >= e:", "if est is not None:"),
+    "own Aggregators skip the loss test": (
+        "                est = self.estimate(cand, k)\n",
+        "                C_ = max(self.cycle(cand), self.D[k])\n                est = (C_, C_ - self.busy(cand, C_))\n"),
+    "scale-up reports every task as moved": (
+        "moved = sum(1 for t, _ in mine if self.where[t][0] != before[t])", "moved = len(mine)"),
+    "released Aggregators stay on a job's own list": (
+        "self.own[k] = [m for m in self.own[k] if m != n]", "self.own[k] = list(self.own[k])"),
+    "exit not reported to pMaster": ("c, local, _ = self.jobs.pop(j)", "c, local, _ = self.jobs[j]"),
+    "demand is the plain sum of execution times": ("        return total / D\n", "        return total\n"),
+    "job registered before the cluster is found": (
+        "        if c is None:\n            return None\n        ctl = self.controllers[c]\n",
+        "        if c is None:\n            self.next_job += 1\n            return None\n        ctl = self.controllers[c]\n"),
+    "tasks assigned by another cluster's controller": (
+        "        ctl = self.controllers[c]\n        local = ctl.add_job(D)\n",
+        "        ctl = self.controllers[0]\n        local = ctl.add_job(D)\n"),
+    "a cluster's book counts every job": (
+        "            if self.jobs[j][0] == c:\n                total += self.jobs[j][2]",
+        "            if True:\n                total += self.jobs[j][2]"),
     "cluster with the most free time": (
         "return min(ok)[1] if ok else None", "return max(ok)[1] if ok else None"),
     "cluster fit strict": ("ok = [(f, i) for i, f in enumerate(free) if f >= demand]",
@@ -77,7 +100,8 @@ def load(src: str):
 
 def run_pins(mod) -> list:
     """Names of the pins that fail against the given copy of the oracle."""
-    saved = {k: getattr(T, k) for k in ("SchedulerOracle", "iteration_duration", "loss", "LOSS_LIMIT_DEFAULT")}
+    saved = {k: getattr(T, k) for k in ("SchedulerOracle", "PMasterOracle", "iteration_duration", "loss",
+                                        "LOSS_LIMIT_DEFAULT")}
     failed = []
 
     def too_long(signum, frame):
