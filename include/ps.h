@@ -66,7 +66,8 @@ enum {
   PS_ERR_HIP = -11,        /* a HIP runtime call failed; see ps_last_error */
   PS_ERR_CAPACITY = -12,   /* an output array is too small; the needed count is reported */
   PS_ERR_NOT_OWNER = -13,  /* the block's master copy is not (or no longer) held by this context */
-  PS_ERR_BUSY = -14        /* the block has pushes pending: it cannot start to migrate now */
+  PS_ERR_BUSY = -14,       /* the block has pushes pending: it cannot start to migrate now */
+  PS_ERR_NO_ROOM = -15     /* scheduling: no Aggregator cluster has room for the job (ps_sched.h) */
 };
 
 /* Where a block's master copy is, as seen by one context. */

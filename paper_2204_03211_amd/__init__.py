@@ -17,4 +17,4 @@ from .binding import (  # noqa: F401
     WaveStats,
     load_library,
 )
-from .sched_binding import Scheduler  # noqa: F401,E402
+from .sched_binding import PMaster, Scheduler  # noqa: F401,E402

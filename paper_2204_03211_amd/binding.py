@@ -21,7 +21,7 @@ ERRORS = {
     -1: "PS_ERR_ARG", -2: "PS_ERR_BAD_JOB", -3: "PS_ERR_BAD_BLOCK", -4: "PS_ERR_BAD_WORKER",
     -5: "PS_ERR_DUP_PUSH", -6: "PS_ERR_NOT_READY", -7: "PS_ERR_DUP_BLOCK", -8: "PS_ERR_ALIGN",
     -9: "PS_ERR_NOMEM", -10: "PS_ERR_NO_DEVICE", -11: "PS_ERR_HIP", -12: "PS_ERR_CAPACITY",
-    -13: "PS_ERR_NOT_OWNER", -14: "PS_ERR_BUSY",
+    -13: "PS_ERR_NOT_OWNER", -14: "PS_ERR_BUSY", -15: "PS_ERR_NO_ROOM",
 }
 OWNER_HERE, OWNER_LEAVING, OWNER_ELSEWHERE = 0, 1, 2
 

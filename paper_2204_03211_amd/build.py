@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libps_agg.so")
-SOURCES = ["ps_service.cpp", "ps_sched.cpp", "ps_kernels.hip"]
+SOURCES = ["ps_service.cpp", "ps_sched.cpp", "ps_pmaster.cpp", "ps_kernels.hip"]
 HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(ROOT, "include", "ps.h"),
            os.path.join(ROOT, "include", "ps_sched.h")]
 

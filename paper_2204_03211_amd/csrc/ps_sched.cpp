@@ -37,6 +37,7 @@ struct ps_sched {
   std::vector<double> D;        // per job; <= 0 once the job has left
   std::vector<Task> tasks;
   std::vector<Agg> aggs;
+  std::map<int32_t, std::vector<int32_t>> own;  // job -> Aggregators added for it by scale-up, oldest first
 
   bool job_ok(int32_t j) const { return j >= 0 && (size_t)j < D.size() && D[j] > 0; }
   bool agg_ok(int32_t n) const { return n >= 0 && (size_t)n < aggs.size() && aggs[n].live; }
@@ -80,6 +81,26 @@ struct ps_sched {
     double best_f = 0.0;
     for (int32_t n = 0; n < (int32_t)aggs.size(); ++n) {
       if (!aggs[n].live || n == exclude) continue;
+      double C, F;
+      if (!estimate(n, k, &C, &F)) continue;
+      if (F >= e && (best < 0 || F < best_f)) { best = n; best_f = F; }
+    }
+    return best;
+  }
+  // Hand an Aggregator back; no job keeps it as one of its own.
+  void release(int32_t n) {
+    aggs[n].live = false;
+    for (auto it = own.begin(); it != own.end();) {
+      auto& v = it->second;
+      v.erase(std::remove(v.begin(), v.end(), n), v.end());
+      it = v.empty() ? own.erase(it) : std::next(it);
+    }
+  }
+  int32_t choose_excluding(int32_t k, double e, const std::vector<int32_t>& skip) const {
+    int32_t best = -1;
+    double best_f = 0.0;
+    for (int32_t n = 0; n < (int32_t)aggs.size(); ++n) {
+      if (!aggs[n].live || std::find(skip.begin(), skip.end(), n) != skip.end()) continue;
       double C, F;
       if (!estimate(n, k, &C, &F)) continue;
       if (F >= e && (best < 0 || F < best_f)) { best = n; best_f = F; }
@@ -190,9 +211,10 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
     a.by_job.erase(it);
   }
   s->D[job] = -1.0;
+  s->own.erase(job);
   for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n)
     if (s->aggs[n].live && s->aggs[n].by_job.empty()) {
-      s->aggs[n].live = false;
+      s->release(n);
       released.push_back(n);
     }
   for (;;) {
@@ -206,7 +228,7 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
       if (victim < 0 || l < load || (l == load && n > victim)) { victim = n; load = l; }
     }
     if (live <= 1 || !s->drain(victim)) break;
-    s->aggs[victim].live = false;
+    s->release(victim);
     released.push_back(victim);
   }
   if (out_n) *out_n = (int32_t)released.size();
@@ -214,22 +236,36 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
   return PS_OK;
 } PS_NO_THROW
 
-int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator) try {
+int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggregator, int32_t* out_moved) try {
   if (!s) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
-  std::vector<int32_t> mine;
+  std::vector<int32_t> mine, before;
   for (int32_t t = 0; t < (int32_t)s->tasks.size(); ++t)
     if (s->tasks[t].live && s->tasks[t].job == job) mine.push_back(t);
-  for (int32_t t : mine) s->unplace(t);
-  const int32_t fresh = s->allocate();
   for (int32_t t : mine) {
-    int32_t n = s->choose(job, s->tasks[t].e, -1);
+    before.push_back(s->tasks[t].agg);
+    s->unplace(t);
+  }
+  const int32_t fresh = s->allocate();
+  s->own[job].push_back(fresh);
+  for (int32_t t : mine) {
+    const double e = s->tasks[t].e;
+    int32_t n = -1;
+    // the Aggregators added for this job come first, oldest first
+    for (int32_t cand : s->own[job]) {
+      double C, F;
+      if (s->estimate(cand, job, &C, &F) && F >= e) { n = cand; break; }
+    }
+    if (n < 0) n = s->choose_excluding(job, e, s->own[job]);
     if (n < 0) n = s->allocate();
     s->place(n, t);
   }
-  for (auto& a : s->aggs)
-    if (a.live && a.by_job.empty()) a.live = false;
+  for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n)
+    if (s->aggs[n].live && s->aggs[n].by_job.empty()) s->release(n);
+  int32_t moved = 0;
+  for (size_t i = 0; i < mine.size(); ++i) moved += s->tasks[mine[i]].agg != before[i] ? 1 : 0;
   if (out_new_aggregator) *out_new_aggregator = fresh;
+  if (out_moved) *out_moved = moved;
   return PS_OK;
 } PS_NO_THROW
 

@@ -501,6 +501,7 @@ const char* ps_strerror(int32_t s) {
     case PS_ERR_CAPACITY: return "output array too small";
     case PS_ERR_NOT_OWNER: return "block's master copy is not held by this context";
     case PS_ERR_BUSY: return "block has pushes pending";
+    case PS_ERR_NO_ROOM: return "no Aggregator cluster has room for the job";
     default: return "unknown status";
   }
 }

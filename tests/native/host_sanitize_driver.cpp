@@ -128,8 +128,9 @@ static void scheduler_rounds(uint64_t seed) {
       const int32_t rc = ps_sched_cycle_plan(s, n, waves.data(), 64, &nw, js.data(), 512, &nj);
       CHECK(rc == PS_OK || rc == PS_ERR_CAPACITY);
     } else if (r < 94) {
-      int32_t fresh = -1;
-      CHECK(ps_sched_scale_up_job(s, live[rng() % live.size()], &fresh) == PS_OK);
+      int32_t fresh = -1, moved = -1;
+      CHECK(ps_sched_scale_up_job(s, live[rng() % live.size()], &fresh, &moved) == PS_OK);
+      CHECK(moved >= 0);
     } else {
       const size_t i = rng() % live.size();
       int32_t rel[64], nrel = 0;
@@ -140,9 +141,49 @@ static void scheduler_rounds(uint64_t seed) {
   ps_sched_destroy(s);
 }
 
+static void pmaster_rounds(uint64_t seed) {
+  std::mt19937_64 rng(seed);
+  ps_pmaster* m = nullptr;
+  CHECK(ps_pmaster_create(0.0, &m) == PS_OK);
+  for (int c = 0; c < 3; ++c) CHECK(ps_pmaster_add_cluster(m, 1.0 + (double)(rng() % 6) / 2.0, nullptr) == PS_OK);
+  std::vector<int32_t> live;
+  const double Ds[] = {3, 4, 5, 6, 7.5, 9, 10, 12, 24};
+  for (int step = 0; step < 200; ++step) {
+    const unsigned r = (unsigned)(rng() % 100);
+    if (r < 55 || live.empty()) {
+      const double D = Ds[rng() % 9];
+      std::vector<double> e(1 + rng() % 8);
+      for (double& x : e) x = (double)(1 + rng() % 23) * D / 64.0;
+      std::vector<int32_t> t(e.size()), a(e.size());
+      int32_t j = -1, c = -1;
+      const int32_t rc = ps_pmaster_forward_job(m, D, e.data(), (int32_t)e.size(), &j, &c, t.data(), a.data());
+      CHECK(rc == PS_OK || rc == PS_ERR_NO_ROOM);
+      if (rc == PS_OK) {
+        live.push_back(j);
+        ps_sched* ctl = ps_pmaster_controller(m, c);
+        CHECK(ctl != nullptr);
+        int32_t where = -1;
+        CHECK(ps_sched_task_info(ctl, t[0], &where, nullptr, nullptr) == PS_OK && where == a[0]);
+      }
+    } else if (r < 75) {
+      int32_t fresh = -1, moved = -1;
+      CHECK(ps_pmaster_scale_up_job(m, live[rng() % live.size()], &fresh, &moved) == PS_OK);
+    } else {
+      const size_t i = rng() % live.size();
+      int32_t rel[64], nrel = 0, c = -1;
+      CHECK(ps_pmaster_job_exit(m, live[i], &c, rel, 64, &nrel) == PS_OK);
+      live.erase(live.begin() + (long)i);
+    }
+    ps_pmaster_cluster_stats cs{};
+    CHECK(ps_pmaster_cluster_info(m, (int32_t)(rng() % 3), &cs) == PS_OK);
+  }
+  ps_pmaster_destroy(m);
+}
+
 int main() {
   for (uint64_t seed = 1; seed <= 40; ++seed) service_rounds(seed);
   for (uint64_t seed = 1; seed <= 10; ++seed) scheduler_rounds(seed);
+  for (uint64_t seed = 1; seed <= 10; ++seed) pmaster_rounds(seed);
   std::printf("host sanitize driver: ok\n");
   return 0;
 }

@@ -35,7 +35,7 @@ def test_version_and_strerror_without_device():
 def test_scheduler_symbols_are_exported():
     from paper_2204_03211_amd.sched_binding import SCHED_EXPORTS
     names = declared_functions("ps_sched.h")
-    assert len(names) == 14
+    assert len(names) == 24
     lib = load_library()
     for n in names:
         assert getattr(lib, n) is not None, n

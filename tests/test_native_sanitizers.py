@@ -22,6 +22,7 @@ def test_service_and_scheduler_host_code_is_clean_under_asan_ubsan():
                "-I", os.path.join(ROOT, "include"),
                os.path.join(ROOT, "tests", "native", "host_sanitize_driver.cpp"),
                os.path.join(CSRC, "ps_service.cpp"), os.path.join(CSRC, "ps_sched.cpp"),
+               os.path.join(CSRC, "ps_pmaster.cpp"),
                "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", "-lpthread", "-o", exe]
         subprocess.check_call(cmd)
         env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=1", UBSAN_OPTIONS="print_stacktrace=1")

@@ -6,8 +6,8 @@ from fractions import Fraction as Fr
 import numpy as np
 import pytest
 
-from oracle.scheduler import SchedulerOracle
-from paper_2204_03211_amd import PsError, Scheduler
+from oracle.scheduler import PMasterOracle, SchedulerOracle
+from paper_2204_03211_amd import PMaster, PsError, Scheduler
 
 
 def test_toy_examples_through_the_c_abi():
@@ -103,7 +103,8 @@ def test_random_sequences_match_the_oracle(seed):
                 assert s.estimate(n, j) == o.estimate(n, j)
             assert s.assign(j, e) == o.assign(j, e)
         elif r < 0.95:
-            continue    # scale-up: the oracle's reading changed; the library follows in the next commit
+            j = int(rng.choice(live))
+            assert s.scale_up_job(j) == o.scale_up_job(j)
         else:
             j = live.pop(int(rng.integers(len(live))))
             assert s.remove_job(j) == o.remove_job(j)
@@ -111,6 +112,92 @@ def test_random_sequences_match_the_oracle(seed):
             compare(o, s)
     compare(o, s)
     assert len(o.aggs) >= 1 or not live
+
+
+def test_scale_up_through_the_c_abi_makes_progress_and_ends():
+    """The case that used to be a no-op: a job on an Aggregator filled 10 of 10
+    must sit elsewhere after one step; the loop 'while slow and moved' ends."""
+    s = Scheduler()
+    a, b = s.add_job(10.0), s.add_job(10.0)
+    ta = [s.assign(a, 2.0)[0] for _ in range(3)]
+    tb = [s.assign(b, 2.0)[0] for _ in range(2)]
+    assert s.aggregators() == [0] and s.aggregator_info(0).free_time == 0.0
+    assert s.scale_up_job(b) == (1, 2)
+    assert [s.task_info(t)[0] for t in tb] == [1, 1] and [s.task_info(t)[0] for t in ta] == [0, 0, 0]
+    steps = 1
+    while True:
+        fresh, moved = s.scale_up_job(b)
+        steps += 1
+        if moved == 0:
+            break
+    assert steps == 2 and s.aggregators() == [0, 1]
+    with pytest.raises(PsError):
+        s.scale_up_job(7)
+
+
+def compare_pmaster(o: PMasterOracle, m: PMaster):
+    assert m.n_clusters() == len(o.capacity)
+    for c in range(len(o.capacity)):
+        ci = m.cluster_info(c)
+        assert (ci.capacity, ci.used, ci.free_resource) == (o.capacity[c], o.used(c), o.free(c))
+        assert ci.n_jobs == sum(1 for j in o.jobs.values() if j[0] == c)
+        assert ci.n_aggregators == len(o.controllers[c].aggs)
+        compare(o.controllers[c], m.controller(c))
+    for j, w in o.jobs.items():
+        assert m.job_info(j) == w
+
+
+def test_pmaster_hand_cases_through_the_c_abi():
+    m = PMaster()
+    assert [m.add_cluster(c) for c in (2.0, 1.0, 3.0)] == [0, 1, 2]
+    assert m.forward_job(10.0, [2.0, 2.0, 1.0]) == (0, 1, [(0, 0), (1, 0), (2, 0)])   # sufficient but least
+    assert m.forward_job(10.0, [4.0, 4.0]) == (1, 0, [(0, 0), (1, 0)])
+    assert m.forward_job(5.0, [5.0, 5.0, 5.0, 2.0]) is None                             # none fits
+    assert m.cluster_info(1).free_resource == 0.5 and m.cluster_info(1).n_jobs == 1
+    assert m.job_exit(0) == (1, [0])                                                    # exit frees the room
+    assert m.cluster_info(1).free_resource == 1.0 and m.cluster_info(1).n_jobs == 0
+    with pytest.raises(PsError):
+        m.job_exit(0)
+    with pytest.raises(PsError):
+        m.forward_job(10.0, [])
+    with pytest.raises(PsError):
+        m.forward_job(10.0, [1.0, -1.0])
+    with pytest.raises(PsError):
+        m.add_cluster(0.0)
+    with pytest.raises(PsError):
+        m.controller(9)
+    assert m.forward_job(10.0, [9.0])[1] == 1                                           # 0.9 into the freed cluster
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_pmaster_random_sequences_match_the_oracle(seed):
+    rng = np.random.default_rng(100 + seed)
+    limit = float(rng.choice([0.05, 0.1, 0.2]))
+    o, m = PMasterOracle(limit), PMaster(limit)
+    for _ in range(int(rng.integers(2, 5))):
+        cap = float(rng.integers(2, 9)) / 2.0
+        assert o.add_cluster(cap) == m.add_cluster(cap)
+    durations = [3.0, 4.0, 5.0, 6.0, 7.5, 9.0, 10.0, 12.0, 24.0]
+    live = []
+    for step in range(120):
+        r = rng.random()
+        if r < 0.55 or not live:
+            D = float(rng.choice(durations))
+            es = [float(rng.integers(1, 24)) * D / 64.0 for _ in range(int(rng.integers(1, 9)))]
+            got, want = m.forward_job(D, es), o.forward_job(D, es)
+            assert got == want
+            if want is not None:
+                live.append(want[0])
+        elif r < 0.75:
+            j = int(rng.choice(live))
+            assert m.scale_up_job(j) == o.scale_up_job(j)
+        else:
+            j = live.pop(int(rng.integers(len(live))))
+            assert m.job_exit(j) == o.job_exit(j)
+        if step % 6 == 0:
+            compare_pmaster(o, m)
+    compare_pmaster(o, m)
+    assert sorted(o.jobs) == sorted(live)
 
 
 def test_assignment_rate_is_job_event_scale():
