@@ -128,8 +128,9 @@ typedef struct ps_block_info {
 } ps_block_info;
 
 typedef struct ps_block_stats {
-  double grad_norm2;      /* sum_i S_i^2 of the block's last aggregation */
-  int64_t round;          /* round that value belongs to (0 = never aggregated) */
+  double grad_norm2;      /* sum_i S_i^2 of the block's last completed aggregation */
+  int64_t round;          /* the block's round counter after that aggregation, written by
+                             the GPU together with the value (0 = never aggregated) */
 } ps_block_stats;
 
 typedef struct ps_wave_stats {
@@ -194,7 +195,8 @@ int32_t ps_register_shadow_job(ps_ctx* ctx, const int64_t* layer_numel, int32_t 
                                float lr, float momentum, float wd, void* stream, ps_job_t* out_job,
                                int32_t* out_n_blocks);
 
-/* Forget a job.  Its arena space is reused only if it was the most recently
+/* Job exit (Section 3.3.2: when a job leaves, what it held is given back).
+ * Forget a job.  Its arena space is reused only if it was the most recently
  * registered live job (the arena is a stack).  Pending pushes are dropped.
  * Waves that name the job must have completed (synchronise their streams first):
  * the job's telemetry memory is released here and its arena space may be handed
@@ -205,6 +207,11 @@ int32_t ps_unregister_job(ps_ctx* ctx, ps_job_t job);
 int32_t ps_job_n_blocks(ps_ctx* ctx, ps_job_t job);
 int64_t ps_job_flat_numel(ps_ctx* ctx, ps_job_t job);
 
+/* One row of the table that says where a piece of a job's state lives and in
+ * what condition: the counterpart of the agent's mapping from (job ID, tensor
+ * ID) to the Aggregator holding the tensor (Section 3.1; Appendix A), at block
+ * granularity, with the owner field a pull response would carry during a
+ * migration (Appendix B). */
 int32_t ps_job_block_info(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_info* out);
 
 /* --- push (worker -> service) -------------------------------------------- */
@@ -322,9 +329,15 @@ int32_t ps_pull_copy(ps_ctx* ctx, ps_job_t job, int32_t block, float* dst_dev, v
 int32_t ps_pull_flat(ps_ctx* ctx, ps_job_t job, const float** out_param_dev,
                      const float** out_mom_dev, int64_t* out_flat_numel);
 
-/* Telemetry of a block's last aggregation.  The value is written by the GPU
- * into host-visible memory at the end of the wave: the caller must have
- * synchronised the wave's stream before reading. */
+/* Telemetry of a block's last aggregation: what the service measures about the
+ * aggregations it runs, for whoever schedules them (the paper's job and server
+ * profilers, Section 3.1, whose figures feed the assignment scheme of Section
+ * 3.3.1; the quantity itself, the squared norm of the aggregated gradient, is
+ * this library's choice).  The GPU writes the value together with the round it
+ * belongs to, in one 16-byte store into host-visible memory, at the end of the
+ * wave; the call reads that pair.  To see the round just enqueued, synchronise
+ * the wave's stream first; without that the pair is that of an earlier round,
+ * with its own round number. */
 int32_t ps_telemetry(ps_ctx* ctx, ps_job_t job, int32_t block, ps_block_stats* out);
 
 /* --- migration of a block's master copy between contexts ------------------- */
@@ -382,8 +395,9 @@ int32_t ps_timing_read(ps_ctx* ctx, ps_timing* out);
 
 /* Static, never NULL. */
 const char* ps_strerror(int32_t status);
-/* Text of the last HIP failure seen by this context ("" if none).  Valid until
- * the next call on the context. */
+/* Detail of the last failure this context reported with PS_ERR_HIP, or with
+ * PS_ERR_CAPACITY from ps_aggregate_noalloc ("" if none).  Valid until the next
+ * call on the context. */
 const char* ps_last_error(ps_ctx* ctx);
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t ps_version(void);

@@ -9,16 +9,26 @@
 // One block of one job as the kernels see it: a 64-byte header followed
 // directly by the block's W gradient pointers (worker order).  Header and
 // pointers are fetched together once a tile names the record.
+// Telemetry of one block as the GPU leaves it in host-visible memory: the value
+// and the round it belongs to, written together with one 16-byte store.
+struct PsStat {
+  double norm2;   // sum S^2 of the block's last aggregation
+  int64_t round;  // the block's round counter after that aggregation
+};
+static_assert(sizeof(PsStat) == 16, "value and round travel in one 16-byte store");
+
 struct PsBlockRec {
   float* p;          // parameter shard (device, 256-byte aligned)
   float* v;          // momentum shard
-  double* stat;      // where sum S^2 of this block goes (host-visible memory)
+  PsStat* stat;      // where this block's telemetry goes (host-visible memory, 16-byte aligned)
   uint32_t n;        // elements in the block
   uint32_t W;        // workers
   uint32_t tile0;    // large path: first of this block's entries in the tile-partials array
   uint32_t ntiles;   // large path: number of tiles
   float lr, mu, wd;
-  uint32_t pad_[3];
+  uint32_t pad_;
+  int64_t round0;    // round the block reaches in the wave these tables were built for;
+                     // a later wave that reuses the tables adds the number of reuses
   // const float* grad[W] follows
 };
 static_assert(sizeof(PsBlockRec) == 64, "record header must stay 64 bytes");
@@ -103,6 +113,7 @@ struct PsWaveTables {
   const uint32_t* large_recs;    // record offsets of large-path blocks
   uint32_t n_large_blocks;
   bool fp_contract;
+  int64_t round_add;             // waves launched with these tables before this one
   // optional hipEvent_t handles recorded before the first launch, after the
   // aggregation launches, and after the telemetry reduction (NULL = no timing)
   void* ev[3];

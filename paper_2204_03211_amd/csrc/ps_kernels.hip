@@ -75,6 +75,13 @@ __device__ __forceinline__ double update4(f32x4 s, f32x4& p, f32x4& v, float lr,
   return a;
 }
 
+// Value and round leave together in one 16-byte store, so that a reader never
+// pairs a new round with an old value.
+__device__ __forceinline__ void put_stat(PsStat* dst, double norm2, int64_t round) {
+  const PsStat s{norm2, round};
+  *reinterpret_cast<i32x4*>(dst) = __builtin_bit_cast(i32x4, s);
+}
+
 __device__ __forceinline__ double wave_sum(double a) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) a += __shfl_xor(a, m, 64);
@@ -188,7 +195,8 @@ __device__ __forceinline__ f32x4 gload4(const float* a) {
 
 template <bool FMA>
 __device__ __forceinline__ void small_bin(const unsigned char* __restrict__ recs,
-                                          const PsSmallEntry* __restrict__ entries, PsBin bin) {
+                                          const PsSmallEntry* __restrict__ entries, PsBin bin,
+                                          long long round_add) {
   __shared__ PsBlockRec sd[PS_BIN_MAX_BLOCKS];
   __shared__ uint32_t srec[PS_BIN_MAX_BLOCKS];
   __shared__ uint32_t qs[PS_BIN_MAX_BLOCKS + 1];   // first quad of each entry
@@ -273,7 +281,7 @@ __device__ __forceinline__ void small_bin(const unsigned char* __restrict__ recs
     double a = 0.0;
     for (uint32_t q = qs[j] + lane; q < qs[j + 1]; q += 64) a += qpart[q];
     a = wave_sum(a);
-    if (lane == 0) *sd[j].stat = a;
+    if (lane == 0) put_stat(sd[j].stat, a, sd[j].round0 + round_add);
   }
 }
 
@@ -291,10 +299,11 @@ __global__ __launch_bounds__(PS_WG, PS_MIN_WAVES) void ps_agg_wave(const unsigne
                                                      double* __restrict__ tile_part,
                                                      const PsSmallEntry* __restrict__ entries,
                                                      const PsBin* __restrict__ bins,
-                                                     uint32_t n_bins, uint32_t hold_ticks) {
+                                                     uint32_t n_bins, uint32_t hold_ticks,
+                                                     long long round_add) {
   const uint32_t b = blockIdx.x;
   if (b < n_bins) {
-    small_bin<FMA>(recs, entries, bins[b]);
+    small_bin<FMA>(recs, entries, bins[b], round_add);
   } else {
     const uint32_t t = tile_begin + (b - n_bins);
     large_tile<W, FMA>(recs, tiles[t], t, tile_part, hold_ticks);
@@ -307,7 +316,8 @@ __global__ __launch_bounds__(PS_WG, PS_MIN_WAVES) void ps_agg_wave(const unsigne
 __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __restrict__ recs,
                                                         const uint32_t* __restrict__ large_recs,
                                                         uint32_t n_large,
-                                                        const double* __restrict__ tile_part) {
+                                                        const double* __restrict__ tile_part,
+                                                        long long round_add) {
   const uint32_t lane = threadIdx.x & 63;
   const uint32_t b = blockIdx.x * (PS_WG / 64) + (threadIdx.x >> 6);
   if (b >= n_large) return;  // whole wavefront leaves together
@@ -316,7 +326,7 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
   double a = 0.0;
   for (uint32_t t = lane; t < d->ntiles; t += 64) a += tile_part[d->tile0 + t];
   a = wave_sum(a);
-  if (lane == 0) *d->stat = a;
+  if (lane == 0) put_stat(d->stat, a, d->round0 + round_add);
 }
 
 // ---------------------------------------------------------------------------
@@ -366,7 +376,8 @@ template <int W, bool FMA>
 hipError_t launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
                       uint32_t n_bins, uint32_t hold_ticks) {
   hipLaunchKernelGGL((ps_agg_wave<W, FMA>), dim3(n_tiles + n_bins), dim3(PS_WG), 0, stream, t.recs,
-                     t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins, hold_ticks);
+                     t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins, hold_ticks,
+                     (long long)t.round_add);
   return hipGetLastError();
 }
 
@@ -510,7 +521,7 @@ int ps_launch_wave(const PsWaveTables& t, void* stream_, uint32_t* launched) {
   if (t.n_large_blocks) {
     const uint32_t per = PS_WG / 64;
     hipLaunchKernelGGL(ps_block_norms, dim3((t.n_large_blocks + per - 1) / per), dim3(PS_WG), 0,
-                       stream, t.recs, t.large_recs, t.n_large_blocks, t.tile_part);
+                       stream, t.recs, t.large_recs, t.n_large_blocks, t.tile_part, (long long)t.round_add);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     *launched += 1;

@@ -59,8 +59,7 @@ struct Job {
   uint64_t arena_bytes = 0;
   float* p = nullptr;
   float* v = nullptr;
-  double* stat = nullptr;        // host-visible, one double per block
-  std::vector<int64_t> stat_round; // host only: round each telemetry value belongs to
+  PsStat* stat = nullptr;        // host-visible, one {value, round} per block, written by the GPU
 };
 
 // HIP events bracketing the phases of one measured wave.
@@ -74,6 +73,10 @@ constexpr int kTimingSets = 8;
 
 struct Plan {
   std::vector<uint64_t> sig;           // what the tables depend on: the list and its gradient pointers
+  std::vector<ps_block_ref> list;      // the list itself, and the context's pointer generation when the
+  uint64_t ptr_gen = 0;                //   tables were built: equal list + equal generation = equal sig
+  std::vector<int64_t> round_at_build; // per list position: the block's round before the first wave
+  int64_t uses = 0;                    // waves launched with these tables
   std::vector<unsigned char> recs;     // PsBlockRec + W pointers per listed block
   std::vector<uint32_t> rec_of;        // record offset (8-byte units) per list position
   std::vector<uint32_t> large_order;   // list positions of large-path blocks, launch order
@@ -111,6 +114,7 @@ struct ps_ctx {
   std::vector<Job> jobs;
   uint64_t arena_top = 0;
   uint64_t wave_counter = 0;
+  uint64_t ptr_gen = 1;          // bumped whenever a push records a pointer other than the one before
   Slot slots[kSlots];
   int next_slot = 0;
   int last_slot = -1;            // slot of the most recent wave (candidate for reuse)
@@ -217,13 +221,26 @@ int32_t hip_fail(ps_ctx* c, hipError_t e, const char* what) {
     if (e_ != hipSuccess) return hip_fail(c, e_, #call); \
   } while (0)
 
-// Validate a block list; gather into c->sig what a plan for it depends on.
-// Changes nothing else but c->wave_counter and the blocks' duplicate stamps.
-int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pushes) {
+// What a plan for a (validated) list depends on besides the context's fixed
+// layout: the blocks named and the gradient pointers pushed for them.
+void gather_signature(ps_ctx* c, const ps_block_ref* list, int64_t n) {
+  c->sig.clear();
+  for (int64_t i = 0; i < n; ++i) {
+    const Job& j = c->jobs[list[i].job];
+    const Block& b = j.blocks[list[i].block];
+    c->sig.push_back(((uint64_t)(uint32_t)list[i].job << 32) | (uint32_t)list[i].block);
+    for (int32_t w = 0; w < j.W; ++w)
+      c->sig.push_back((b.mask >> w) & 1u ? (uint64_t)reinterpret_cast<uintptr_t>(b.grad[w]) : 0);
+  }
+}
+
+// Validate a block list.  Changes nothing but c->wave_counter, the blocks'
+// duplicate stamps and (if asked) c->sig.
+int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_pushes,
+                      bool gather_sig = true) {
   if (n < 0 || (n > 0 && !list)) return PS_ERR_ARG;
   if (n > 0x7FFFFFF0ll) return PS_ERR_ARG;
   const uint64_t stamp = ++c->wave_counter;
-  c->sig.clear();
   for (int64_t i = 0; i < n; ++i) {
     Job* j = find_job(c, list[i].job);
     if (!j) return PS_ERR_BAD_JOB;
@@ -233,10 +250,8 @@ int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_
     b.wave_stamp = stamp;
     if (b.owner != PS_OWNER_HERE) return PS_ERR_NOT_OWNER;
     if (need_pushes && b.mask != j->full_mask) return PS_ERR_NOT_READY;
-    c->sig.push_back(((uint64_t)(uint32_t)list[i].job << 32) | (uint32_t)list[i].block);
-    for (int32_t w = 0; w < j->W; ++w)
-      c->sig.push_back((b.mask >> w) & 1u ? (uint64_t)reinterpret_cast<uintptr_t>(b.grad[w]) : 0);
   }
+  if (gather_sig) gather_signature(c, list, n);
   return PS_OK;
 }
 
@@ -245,6 +260,10 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   P.recs.clear(); P.rec_of.clear(); P.large_order.clear(); P.tiles.clear(); P.chunks.clear();
   P.small_entries.clear(); P.bins.clear(); P.large_recs.clear();
   P.stats = ps_wave_stats{};
+  P.list.assign(list, list + n);
+  P.ptr_gen = c->ptr_gen;
+  P.round_at_build.resize((size_t)n);
+  P.uses = 0;
   const uint32_t small_max = c->cfg.small_block_elems;
 
   // one record per listed block, in list order; small blocks go to bins
@@ -257,10 +276,12 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   for (int64_t i = 0; i < n; ++i) {
     Job& j = c->jobs[list[i].job];
     Block& b = j.blocks[list[i].block];
+    P.round_at_build[(size_t)i] = b.round;
     PsBlockRec d{};
     d.p = j.p ? j.p + b.flat_off : nullptr;
     d.v = j.v ? j.v + b.flat_off : nullptr;
     d.stat = j.stat ? j.stat + list[i].block : nullptr;
+    d.round0 = b.round + 1;
     d.n = (uint32_t)b.numel;
     d.W = (uint32_t)j.W;
     d.lr = j.lr; d.mu = j.mu; d.wd = j.wd;
@@ -610,7 +631,7 @@ static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_lay
     char* base = static_cast<char*>(c->cfg.arena_dev) + j.arena_off;
     j.p = reinterpret_cast<float*>(base);
     j.v = j.p + j.flat_numel;
-    PS_HIP(c, hipHostMalloc((void**)&j.stat, nb * sizeof(double), hipHostMallocDefault));
+    PS_HIP(c, hipHostMalloc((void**)&j.stat, nb * sizeof(PsStat), hipHostMallocDefault));
     hipStream_t s = static_cast<hipStream_t>(stream);
     // parameters' padding and all momentum start at zero
     hipError_t e = (hipError_t)ps_launch_zero(j.p, j.arena_bytes / 4, stream);
@@ -628,11 +649,10 @@ static int32_t register_job(ps_ctx* c, const int64_t* layer_numel, int32_t n_lay
       return hip_fail(c, e, "initialising the job's shards");
     }
   } else {
-    j.stat = new (std::nothrow) double[nb];
+    j.stat = new (std::nothrow) PsStat[nb];
     if (!j.stat) return PS_ERR_NOMEM;
   }
-  j.stat_round.assign(nb, 0);
-  for (size_t b = 0; b < nb; ++b) j.stat[b] = 0.0;
+  for (size_t b = 0; b < nb; ++b) j.stat[b] = PsStat{0.0, 0};
   if (shadow)
     for (Block& b : j.blocks) b.owner = PS_OWNER_ELSEWHERE;
   j.live = true;
@@ -667,7 +687,6 @@ int32_t ps_unregister_job(ps_ctx* c, ps_job_t job) try {
   if (j->stat && c->cfg.arena_dev) (void)hipHostFree(j->stat);
   else delete[] j->stat;
   j->stat = nullptr;
-  j->stat_round.clear();
   j->blocks.clear(); j->blocks.shrink_to_fit();
   // pop the arena stack past every dead job on top
   uint64_t top = 0;
@@ -722,6 +741,7 @@ int32_t ps_push(ps_ctx* c, ps_job_t job, int32_t block, int32_t worker, const fl
   Block& b = j->blocks[block];
   if (b.owner != PS_OWNER_HERE) return PS_ERR_NOT_OWNER;
   if ((b.mask >> worker) & 1u) return PS_ERR_DUP_PUSH;
+  if (b.grad[worker] != grad_dev) c->ptr_gen += 1;
   b.grad[worker] = grad_dev;
   b.mask |= 1u << worker;
   return PS_OK;
@@ -737,11 +757,14 @@ int32_t ps_push_flat(ps_ctx* c, ps_job_t job, int32_t worker, const float* grad_
   const uint32_t bit = 1u << worker;
   for (const Block& b : j->blocks)
     if (b.owner == PS_OWNER_HERE && (b.mask & bit)) return PS_ERR_DUP_PUSH;
+  bool changed = false;
   for (Block& b : j->blocks) {
     if (b.owner != PS_OWNER_HERE) continue;  // pushed to whoever owns it
+    if (b.grad[worker] != grad_flat_dev + b.flat_off) changed = true;
     b.grad[worker] = grad_flat_dev + b.flat_off;
     b.mask |= bit;
   }
+  if (changed) c->ptr_gen += 1;
   return PS_OK;
 } PS_NO_THROW
 
@@ -972,14 +995,26 @@ int32_t ps_estimate_wave(ps_ctx* c, const ps_block_ref* list, int64_t n, ps_wave
 static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, void* stream, bool noalloc) {
   if (!c) return PS_ERR_ARG;
   std::lock_guard<std::mutex> g(c->mu);
-  int32_t st = validate_list(c, list, n, /*need_pushes=*/true);
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  PsStaticScratch* ss = noalloc ? c->sscratch : nullptr;
+  ScratchGuard scratch_guard(ss);
+
+  // Steady-state training repeats the same wave with the same gradient buffers:
+  // if the previous wave's tables still describe this one, they are used as they
+  // are.  The candidate: the static array's tables, or the most recent slot's.
+  Slot* cand = noalloc ? &c->static_slot : (c->last_slot >= 0 ? &c->slots[c->last_slot] : nullptr);
+  if (cand && (!cand->valid || (noalloc && (!ss || cand->generation != ss->generation)))) cand = nullptr;
+  // Same list and no push has recorded a new pointer since the tables were
+  // built: the signature is the same without gathering it again.
+  const bool same_list = cand && n > 0 && list && cand->plan.ptr_gen == c->ptr_gen &&
+                         (int64_t)cand->plan.list.size() == n &&
+                         std::memcmp(cand->plan.list.data(), list, (size_t)n * sizeof(ps_block_ref)) == 0;
+  int32_t st = validate_list(c, list, n, /*need_pushes=*/true, /*gather_sig=*/!same_list);
   if (st != PS_OK) return st;
   if (n == 0) return PS_OK;
   if (!c->cfg.arena_dev) return PS_ERR_NO_DEVICE;
-  hipStream_t hs = static_cast<hipStream_t>(stream);
-  PsStaticScratch* ss = noalloc ? c->sscratch : nullptr;
   if (noalloc && !ss) return PS_ERR_NO_DEVICE;
-  ScratchGuard scratch_guard(ss);
+  bool sig_ready = !same_list;
 
   // A shard that arrived by migration must not be updated before its copy is
   // complete (the new owner's consistency rule): order this stream after it.
@@ -994,25 +1029,28 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
     }
   }
 
-  // Steady-state training repeats the same wave with the same gradient buffers:
-  // if the previous wave's tables still describe this one, use them as they are.
   Slot* sp = nullptr;
-  bool reuse = false;
-  if (noalloc) {
-    Slot& ls = c->static_slot;
-    sp = &ls;
-    reuse = ls.valid && ls.generation == ss->generation && ls.plan.sig == c->sig;
-    // the array (tables and tile partials) is shared with whatever used it last
-    if (reuse && ss->in_flight && ss->last_stream != stream)
-      PS_HIP(c, hipStreamWaitEvent(hs, static_cast<hipEvent_t>(ss->last), 0));
-  } else if (c->last_slot >= 0) {
-    Slot& ls = c->slots[c->last_slot];
-    if (ls.valid && ls.plan.sig == c->sig) {
-      sp = &ls;
-      reuse = true;
+  bool reuse = cand && (same_list || cand->plan.sig == c->sig);
+  if (reuse) {
+    // the tables carry each block's round as it was when they were built plus
+    // the number of waves since: that must still be every block's round
+    const Plan& P = cand->plan;
+    for (int64_t i = 0; i < n && reuse; ++i)
+      reuse = c->jobs[list[i].job].blocks[list[i].block].round == P.round_at_build[(size_t)i] + P.uses;
+  }
+  if (reuse) {
+    sp = cand;
+    if (noalloc) {
+      // the array (tables and tile partials) is shared with whatever used it last
+      if (ss->in_flight && ss->last_stream != stream)
+        PS_HIP(c, hipStreamWaitEvent(hs, static_cast<hipEvent_t>(ss->last), 0));
+    } else if (cand->in_flight && cand->stream != hs) {
       // tables and tile partials are shared with the slot's previous wave
-      if (ls.in_flight && ls.stream != hs) PS_HIP(c, hipStreamWaitEvent(hs, ls.done, 0));
+      PS_HIP(c, hipStreamWaitEvent(hs, cand->done, 0));
     }
+  } else {
+    if (noalloc) sp = &c->static_slot;
+    if (!sig_ready) gather_signature(c, list, n);
   }
   TimingSet* ts = nullptr;
   if (c->timing_level > 0 && !noalloc) {
@@ -1059,6 +1097,7 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
   }
   Slot& s = *sp;
   PsWaveTables t = s.tables;
+  t.round_add = s.plan.uses;
   for (int i = 0; i < 3; ++i) t.ev[i] = ts ? ts->ev[i + 1] : nullptr;
   if (ts && !ts->all_phases) t.ev[2] = nullptr;
   uint32_t launched = 0;
@@ -1092,6 +1131,7 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
     c->last_slot = (int)(sp - c->slots);
   }
   s.valid = true;
+  s.plan.uses += 1;
   if (ts) {
     ts->pending = true;
     ts->launches = s.plan.stats.n_launches;
@@ -1103,7 +1143,6 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
     Block& b = j.blocks[list[i].block];
     b.mask = 0;
     b.round += 1;
-    j.stat_round[list[i].block] = b.round;
   }
   return PS_OK;
 }
@@ -1202,8 +1241,18 @@ int32_t ps_telemetry(ps_ctx* c, ps_job_t job, int32_t block, ps_block_stats* out
   Job* j = find_job(c, job);
   if (!j) return PS_ERR_BAD_JOB;
   if (block < 0 || (size_t)block >= j->blocks.size()) return PS_ERR_BAD_BLOCK;
-  out->grad_norm2 = reinterpret_cast<volatile double*>(j->stat)[block];
-  out->round = j->stat_round[block];
+  // The GPU writes value and round with one 16-byte store; read until two
+  // readings agree so that the halves belong together.
+  const volatile PsStat* at = j->stat + block;
+  PsStat a{at->norm2, at->round};
+  for (int tries = 0; tries < 8; ++tries) {
+    const PsStat b{at->norm2, at->round};
+    const bool same = std::memcmp(&a, &b, sizeof(a)) == 0;
+    a = b;
+    if (same) break;
+  }
+  out->grad_norm2 = a.norm2;
+  out->round = a.round;
   return PS_OK;
 } PS_NO_THROW
 
