@@ -30,10 +30,35 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 # HBM bytes per ps_agg_wave launch from rocprofv3 FETCH_SIZE + WRITE_SIZE counters
-# (scaled by a 1 GiB copy), for the default configuration of a workload.  Only
-# valid for the kernel as profiled: set an entry to None when the kernel changes.
-MEASURED_TRAFFIC_PER_LAUNCH = {"packed_wave": 33.966e9 / 110, "vgg16": 6.6493e9 / 17,
-                               "resnet50": 2.0465e9 / 4, "alexnet": 2.9365e9 / 8}
+# (each scaled by what the same counter reads for a 1 GiB copy), for the default
+# configuration of a workload, as recorded under profiles/.  Each entry names the
+# kernel sources it was measured with (kernel_hash()); with other sources the
+# figure says nothing about the loaded kernel and the line reports null.
+MEASURED_TRAFFIC = {
+    "kernel_hash": "none-yet",
+    "per_launch": {"packed_wave": 33.966e9 / 110, "vgg16": 6.6493e9 / 17,
+                   "resnet50": 2.0465e9 / 4, "alexnet": 2.9365e9 / 8},
+}
+
+
+def kernel_hash() -> str:
+    """Hash of the files that define the kernels and their launch shape."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("ps_kernels.hip", "ps_internal.h"):
+        with open(os.path.join(ROOT, "paper_2204_03211_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, default_config: bool, current_hash=None):
+    """Counter traffic per launch for the roofline object, or None when it was
+    not measured for this workload, this configuration or these kernel sources."""
+    if not default_config:
+        return None
+    if (current_hash or kernel_hash()) != MEASURED_TRAFFIC["kernel_hash"]:
+        return None
+    return MEASURED_TRAFFIC["per_launch"].get(workload)
 
 
 def specs_for(name: str):
@@ -243,13 +268,22 @@ def measure(workload: str, args, keep: bool):
     svc.aggregate(svc.pack_wave(gpu.jobs))                   # consume the pushes again
     torch.cuda.synchronize()
 
-    svc.timing_enable(1)                          # two events a wave, around the aggregation launches
+    # the timed region: no library event on the stream, two events around all of it
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record()
     for _ in range(args.steps):
         wave = step()
+    ev1.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    region_ms = ev0.elapsed_time(ev1)
+    # the same steps again, now with two library events a wave on the wave's stream (before the
+    # first and after the last ps_agg_wave launch): the kernel's own time, for the roofline
+    svc.timing_enable(1)
+    for _ in range(args.steps):
+        step()
     tm = svc.timing_read()
     svc.timing_enable(0)
 
@@ -285,12 +319,17 @@ def measure(workload: str, args, keep: bool):
         "roofline": {
             "bound": "hbm", "kernel": "ps_agg_wave", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": (MEASURED_TRAFFIC_PER_LAUNCH.get(workload)
-                        if not (args.small_elems or args.launch_tiles or args.hold_permille) else None),
+            "traffic": measured_traffic(workload, not (args.small_elems or args.launch_tiles or args.hold_permille)),
+            "kernel_hash": kernel_hash(),
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_launch_ms,
             "launches": tm.n_launches, "launches_per_wave": stats.n_launches,
-            "note": "avg_launch_ms = HIP-event time from the first to the last launch of a wave "
-                    "divided by the launches in it, so gaps between launches count",
+            "note": "avg_launch_ms = HIP-event time from the first to the last ps_agg_wave launch of a "
+                    "wave (events on the wave's stream) divided by the launches in it, gaps between "
+                    "launches included, over --steps waves that follow the timed region at once; the "
+                    "timed region itself carries no library event, only one event at either end "
+                    "(timed_region_event_ms: every kernel of the path)",
+            "timed_region_event_ms": region_ms,
+            "timed_region_GB_per_s": stats.algorithmic_bytes * args.steps / (region_ms * 1e-3) / 1e9,
         },
         "ps_agg_wave_ms_per_wave_timed": agg_ms_wave,
         "ps_agg_wave_ms_per_wave": per_wave,
@@ -322,12 +361,17 @@ def main() -> int:
                     help="only the timed steps: skip the wave-by-wave and per-path passes and the "
                          "short single-job runs appended to the packed-wave line")
     ap.add_argument("--copy-calibration", action="store_true")
+    ap.add_argument("--kernel-hash", action="store_true",
+                    help="print the hash of the kernel sources (what a traffic figure must name) and exit")
     ap.add_argument("--migration", action="store_true",
                     help="instead: time moving every block of --workload's first job to a second context")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
     ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
     args = ap.parse_args()
+    if args.kernel_hash:
+        print(kernel_hash())
+        return 0
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
               "and no multi-GPU path exists; run with --gpus 1.", file=sys.stderr)

@@ -80,12 +80,14 @@ _lib = None
 
 
 def load_library() -> C.CDLL:
-    """Load the in-tree library, building it only if no built copy exists.
-    There is no fallback: without the library nothing here works."""
+    """Load the in-tree library; build it first if there is none or if it was
+    not built from the present sources (an edited kernel must never be tested
+    through an old binary).  There is no fallback: without the library, or
+    without a compiler to refresh a stale one, this raises."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _build.is_stale():
         _build.build()
     L = C.CDLL(_build.LIB)
     vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64

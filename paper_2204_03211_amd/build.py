@@ -29,12 +29,32 @@ def hipcc() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
+STAMP = LIB + ".srchash"
+
+
+def source_files():
+    return [os.path.join(CSRC, s) for s in SOURCES] + HEADERS
+
+
+def source_hash(files=None) -> str:
+    """Hash of everything the library is built from: sources, headers, flags.
+    File times are not used: a copied tree has arbitrary ones."""
+    import hashlib
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for f in (files if files is not None else source_files()):
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:20]
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    """True unless the built library was made from exactly the present sources
+    (build() records their hash next to it)."""
+    if not (os.path.exists(LIB) and os.path.exists(STAMP)):
         return True
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, s) for s in SOURCES] + HEADERS
-    return any(os.path.getmtime(d) > t for d in deps)
+    with open(STAMP) as fh:
+        return fh.read().strip() != source_hash()
 
 
 def build(verbose: bool = False) -> str:
@@ -57,8 +77,11 @@ def build(verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + text)
         if verbose and text.strip():
             print(text)
+    stamp = source_hash()          # of what was just compiled
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.check_call(cmd)
+    with open(STAMP, "w") as fh:
+        fh.write(stamp + "\n")
     return LIB
 
 
