@@ -121,7 +121,7 @@ def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
     }
 
 
-def migration_bench(spec, reps: int):
+def migration_bench(spec, reps: int, batched_only: bool = False):
     """Move all blocks of one job from one context to another and back, reps
     times; the time is what a job would wait if nothing hid it (GPU time of the
     announce + copy calls, HIP events on the copy stream)."""
@@ -137,7 +137,7 @@ def migration_bench(spec, reps: int):
     torch.cuda.synchronize()
     times, host = [], []
     src = 0
-    for _ in range(max(reps, 2)):
+    for _ in range(0 if batched_only else max(reps, 2)):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
         a.record()
@@ -149,7 +149,7 @@ def migration_bench(spec, reps: int):
         torch.cuda.synchronize()
         times.append(a.elapsed_time(b))
         src = 1 - src
-    times, host = times[1:], host[1:]
+    times, host = times[1:] or [float("nan")], host[1:] or [float("nan")]
     n_bytes = 8 * spec.n_params
     ms = sum(times) / len(times)
     # the same move as one batched call
@@ -166,7 +166,11 @@ def migration_bench(spec, reps: int):
     out = {"migration": True, "model": spec.model, "blocks": nb, "params": spec.n_params,
            "bytes_moved": n_bytes, "gpu_ms": ms, "host_call_ms": sum(host) / len(host),
            "GB_per_s": n_bytes / ms / 1e6,
-           "batched_gpu_ms": many_ms, "batched_GB_per_s": n_bytes / many_ms / 1e6}
+           "batched_gpu_ms": many_ms, "batched_GB_per_s": n_bytes / many_ms / 1e6,
+           "batched_hbm_traffic_GB_per_s": 2 * n_bytes / many_ms / 1e6,
+           "note": "bytes_moved = 8 bytes per parameter (parameters and momentum); each is read once and "
+                   "written once, so HBM traffic is twice that; times are event times around the host "
+                   "calls, launch latency included"}
     for s in svcs:
         s.close()
     return out
@@ -247,6 +251,7 @@ def measure(workload: str, args, keep: bool):
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     svc = gpu.svc
+    rates = svc.rates()
 
     def step():
         wave = svc.pack_wave(gpu.jobs)                       # a3
@@ -341,6 +346,9 @@ def measure(workload: str, args, keep: bool):
                        "algorithmic_bytes": stats.algorithmic_bytes - stats.small_algorithmic_bytes,
                        **paths["large"]},
         "setup_seconds": t_setup,
+        "rates": {"read_TB_per_s": rates.read_bytes_per_sec / 1e12, "write_TB_per_s": rates.write_bytes_per_sec / 1e12,
+                  "calibrated": bool(rates.calibrated),
+                  "note": "what the library predicts launch phases with; measured at ps_create when calibrated"},
     }
     if not keep:
         gpu.close()
@@ -365,6 +373,8 @@ def main() -> int:
                     help="print the hash of the kernel sources (what a traffic figure must name) and exit")
     ap.add_argument("--migration", action="store_true",
                     help="instead: time moving every block of --workload's first job to a second context")
+    ap.add_argument("--migration-batched", action="store_true",
+                    help="with --migration: only the one-call move of the whole job (for kernel profiles)")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
     ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
@@ -393,7 +403,7 @@ def main() -> int:
         return 0
     specs, seed = specs_for(args.workload)
     if args.migration:
-        print(json.dumps(migration_bench(specs[0], args.steps)))
+        print(json.dumps(migration_bench(specs[0], args.steps, args.migration_batched)))
         return 0
     out, gpu, wave = measure(args.workload, args, keep=True)
     if args.workload == "packed_wave" and not args.no_side_configs:

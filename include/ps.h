@@ -78,8 +78,9 @@ enum {
 };
 
 enum {
-  PS_FLAG_FP_CONTRACT = 1u /* use fused multiply-add in the update (not bit-exact with
+  PS_FLAG_FP_CONTRACT = 1u,/* use fused multiply-add in the update (not bit-exact with
                               the separately rounded definition; error <= 1e-6 relative) */
+  PS_FLAG_NO_CALIBRATION = 2u /* ps_create does not measure the GPU's read rate (see ps_rates) */
 };
 
 typedef struct ps_ctx ps_ctx;
@@ -103,7 +104,7 @@ typedef struct ps_config {
                                  store them only once this fraction (in 1/1000) of the
                                  launch's predicted read time has passed since they
                                  started, so that reads and writes reach HBM in separate
-                                 bursts; 0 = default (1000), negative = no hold, at most 2000 */
+                                 bursts; 0 = default (950), negative = no hold, at most 2000 */
 } ps_config;
 
 typedef struct ps_block_ref {
@@ -144,11 +145,18 @@ typedef struct ps_wave_stats {
   uint64_t small_algorithmic_bytes; /* the part of that in small-path blocks */
   int64_t n_launches;      /* aggregation kernel launches the list is cut into */
   double est_seconds;      /* predicted GPU time of the wave on MI355X: per launch, bytes read
-                              at 7.0 TB/s, then bytes written at 6.0 TB/s, plus 1.5 us; plus
-                              5 us a wave.  Within a few per cent of the measured time for
+                              at the read rate, then bytes written at the write rate (ps_rates:
+                              7.0 and 6.0 TB/s unless measured), plus 1.5 us; plus 5 us a wave.  Within a few per cent of the measured time for
                               waves of tens of megabytes and more; an execution time e_t for
                               ps_sched_assign (the paper's profiler, Section 3.3.1) */
 } ps_wave_stats;
+
+typedef struct ps_rates_info {
+  double read_bytes_per_sec;   /* HBM rate of a launch's read phase */
+  double write_bytes_per_sec;  /* ... and of its write phase */
+  int32_t calibrated;          /* 1 = measured on this GPU, 0 = the built-in MI355X figures (7.0 and 6.0 TB/s) */
+  int32_t reserved_;
+} ps_rates_info;
 
 typedef struct ps_timing {
   int64_t n_waves;     /* waves measured since ps_timing_enable */
@@ -380,6 +388,18 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
                         ps_job_t dst_job, void* stream);
 
 /* --- measurement ------------------------------------------------------------ */
+
+/* The HBM rates behind the launch timing and behind ps_wave_stats.est_seconds
+ * (the service's server profiler, Section 3.1: how fast this Aggregator is).
+ * The built-in figures were fitted on MI355X.  ps_create measures, once per GPU
+ * and process, how this GPU compares: a few read-only launches over the arena
+ * before anything lives in it (median of five readings, about 3 ms in all),
+ * when the arena is at least about 1.4 GB; both rates are scaled by that
+ * reading relative to the reference MI355X's.  With a smaller arena and no
+ * earlier measurement in the process, with a reading outside 0.8 .. 1.15 of
+ * the reference, or with PS_FLAG_NO_CALIBRATION, the built-in figures stand.
+ * The rates change timing only, never results. */
+int32_t ps_rates(ps_ctx* ctx, ps_rates_info* out);
 
 /* Event timing of the waves, for measurement.  on == 1: from now on every
  * ps_aggregate brackets its aggregation launches with two HIP events on the

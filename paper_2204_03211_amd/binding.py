@@ -16,6 +16,7 @@ from . import build as _build
 PS_MAX_W = 32
 PS_OK = 0
 FLAG_FP_CONTRACT = 1
+FLAG_NO_CALIBRATION = 2
 
 ERRORS = {
     -1: "PS_ERR_ARG", -2: "PS_ERR_BAD_JOB", -3: "PS_ERR_BAD_BLOCK", -4: "PS_ERR_BAD_WORKER",
@@ -62,6 +63,11 @@ class WaveStats(C.Structure):
                 ("est_seconds", C.c_double)]
 
 
+class Rates(C.Structure):
+    _fields_ = [("read_bytes_per_sec", C.c_double), ("write_bytes_per_sec", C.c_double),
+                ("calibrated", C.c_int32), ("reserved_", C.c_int32)]
+
+
 class Timing(C.Structure):
     _fields_ = [("n_waves", C.c_int64), ("n_launches", C.c_int64), ("upload_ms", C.c_double),
                 ("agg_ms", C.c_double), ("norms_ms", C.c_double), ("total_ms", C.c_double)]
@@ -73,7 +79,7 @@ EXPORTS = [
     "ps_migrate_many", "ps_estimate_wave",
     "ps_job_n_blocks", "ps_job_flat_numel", "ps_job_block_info", "ps_push", "ps_push_flat",
     "ps_pack_wave", "ps_plan_wave", "ps_aggregate", "ps_aggregate_noalloc", "ps_pull", "ps_pull_momentum", "ps_pull_flat", "ps_pull_copy",
-    "ps_telemetry", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
+    "ps_telemetry", "ps_rates", "ps_timing_enable", "ps_timing_read", "ps_strerror", "ps_last_error", "ps_version",
 ]
 
 _lib = None
@@ -122,6 +128,7 @@ def load_library() -> C.CDLL:
     L.ps_pull_flat.argtypes = [vp, i32, P(vp), P(vp), P(i64)]
     L.ps_pull_copy.argtypes = [vp, i32, i32, vp, vp]
     L.ps_telemetry.argtypes = [vp, i32, i32, P(BlockStats)]
+    L.ps_rates.argtypes = [vp, P(Rates)]
     L.ps_timing_enable.argtypes = [vp, i32]
     L.ps_timing_read.argtypes = [vp, P(Timing)]
     L.ps_strerror.argtypes = [i32]
@@ -343,6 +350,11 @@ class ParameterService:
     def telemetry(self, job: int, block: int) -> BlockStats:
         out = BlockStats()
         self._check(self.L.ps_telemetry(self.ctx, job, block, C.byref(out)))
+        return out
+
+    def rates(self) -> Rates:
+        out = Rates()
+        self._check(self.L.ps_rates(self.ctx, C.byref(out)))
         return out
 
     def timing_enable(self, on: bool) -> None:

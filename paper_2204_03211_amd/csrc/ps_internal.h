@@ -90,14 +90,26 @@ constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path 
 // (hold_ticks) and then write together.
 inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e. whatever is resident
 
-// Sustained pure-read HBM rate measured on MI355X (16-byte non-temporal buffer
-// loads, many streams); used only to predict when a launch's reads end.
+// Rates of the two phases of a launch, fitted on MI355X to the launch times of
+// the aggregation kernel (time = bytes read / READ + bytes written / WRITE +
+// a fixed cost): they predict when a launch's reads end, and how long a wave
+// takes (ps_wave_stats.est_seconds).  A workgroup starts to store when
+// PS_DEFAULT_HOLD_PERMILLE / 1000 of its launch's predicted read time has
+// passed: a little before the last reads are in, measured best at 950 for every
+// worker count (sweep on W = 2, 4, 8, 16: 910..985 within 1 %, 1000 1-2 %
+// slower, 1050 5 % slower).
 constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
-constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 1000;
-// For the predicted time of a wave (ps_wave_stats.est_seconds): sustained
-// pure-write rate in resident-size launches, and the fitted fixed costs.
+constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 950;
 constexpr double PS_WRITE_BYTES_PER_SEC = 6.0e12;
+// What ps_measure_read_rate reads on the MI355X boxes those rates were fitted on
+// (its launches include their fixed cost, so it reads lower than READ).  A
+// context scales both rates by (its GPU's reading / this).
+constexpr double PS_PROBE_NOMINAL_BYTES_PER_SEC = 6.78e12;
 constexpr double PS_EST_LAUNCH_SECONDS = 1.5e-6;
+// A copy's launches write as much as they read; measured on MI355X they are
+// fastest when the stores start at 900/1000 of the predicted read time (800:
+// -3 %, 1000: -2 %, 1100: -6 %, no hold: -10 %).
+constexpr uint32_t PS_COPY_HOLD_PERMILLE = 900;
 constexpr double PS_EST_WAVE_SECONDS = 5.0e-6;
 
 struct PsWaveTables {
@@ -130,9 +142,22 @@ int ps_launch_wave(const PsWaveTables& t, void* stream, uint32_t* launched);
 
 // Enqueue on stream the copy of n floats of parameters and n floats of momentum
 // (both pairs 16-byte aligned) from one context's shards to another's: the
-// TENSOR_COPY of a migration.  Returns a hipError_t value (0 = success).
+// TENSOR_COPY of a migration.  The copy is cut into launches of launch_tiles
+// workgroups (what the chip holds at once; 0 = unknown: one launch); a launch
+// of m tiles keeps what it read for hold_ticks_per_tile * m ticks of the wall
+// clock before it stores (0 = no hold).  Returns a hipError_t value (0 = success).
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
-                   void* stream);
+                   void* stream, uint32_t launch_tiles, double hold_ticks_per_tile);
+// Workgroups of the copy kernel the current device holds at once; 0 if unknown.
+uint32_t ps_resident_copy_workgroups();
+
+// Measure the rate at which launches shaped like the aggregation's read HBM:
+// a few launches of as many workgroups as the chip holds, each reading ten
+// arrays' tiles from the (still unused) arena, timed with events on a stream of
+// their own.  Synchronous.  Returns 0 and the rate, -1 if the arena is too
+// small to give every launch fresh memory (about 1.4 GB are needed) or the
+// device cannot be queried, else a hipError_t value.
+int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_per_sec);
 
 // Enqueue on stream the zeroing of n floats at p (16-byte aligned) with a fill
 // kernel (no memset node, so the call may sit inside a captured graph).

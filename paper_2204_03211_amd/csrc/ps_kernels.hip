@@ -13,6 +13,7 @@
 // for this translation unit regardless of the command line.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "ps_internal.h"
@@ -333,15 +334,21 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
 // Migration copy: a workgroup moves one tile (PS_TILE_ELEMS floats) of the
 // parameter array and the same tile of the momentum array.  All eight loads of
 // a lane are issued before its first store; ragged ends are left to the buffer
-// range check.
+// range check.  Launched like the aggregation: no more workgroups than the chip
+// holds at once, and every workgroup keeps what it has read in registers until
+// the launch's reads are due to be over (hold_ticks of the wall clock after its
+// own start; the clock always advances, so the wait ends).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict__ src_p,
                                                         float* __restrict__ dst_p,
                                                         const float* __restrict__ src_v,
                                                         float* __restrict__ dst_v,
-                                                        unsigned long long n) {
+                                                        unsigned long long n, uint32_t first_tile,
+                                                        uint32_t hold_ticks) {
+  const unsigned long long t_start = wall_clock64();
   constexpr int U = PS_TILE_QUADS_PER_LANE;
-  const unsigned long long at = (unsigned long long)blockIdx.x * PS_TILE_ELEMS;  // < n by the grid's size
+  // < n by the grid's size
+  const unsigned long long at = ((unsigned long long)first_tile + blockIdx.x) * PS_TILE_ELEMS;
   const unsigned long long left = n - at;
   const uint32_t bytes = (uint32_t)(left < PS_TILE_ELEMS ? left : PS_TILE_ELEMS) * 4;
   const uint32_t tid = threadIdx.x;
@@ -354,10 +361,49 @@ __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict_
     b[u] = load4(sv, (u * PS_WG + tid) * 16);
   }
 #pragma unroll
+  for (int u = 0; u < U; ++u) asm volatile("" : "+v"(a[u]), "+v"(b[u]));  // loaded before the wait
+  while ((uint32_t)(wall_clock64() - t_start) < hold_ticks) __builtin_amdgcn_s_sleep(8);
+#pragma unroll
   for (int u = 0; u < U; ++u) {
     store4(dp, (u * PS_WG + tid) * 16, a[u]);
     store4(dv, (u * PS_WG + tid) * 16, b[u]);
   }
+}
+
+// ---------------------------------------------------------------------------
+// Read-rate probe: the read phase of an aggregation launch and nothing else.
+// A workgroup reads one tile of each of `streams` arrays that lie `stride`
+// floats apart (two arrays' loads in flight together, as in tile_body), adds
+// everything up and stores nothing -- unless the sum hits one particular value,
+// which keeps the loads alive for the compiler; the arena it reads is not in
+// use yet, so even that store would do no harm.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(PS_WG) void ps_probe_read(float* __restrict__ base, unsigned long long stride,
+                                                       uint32_t streams, uint32_t first_tile) {
+  constexpr int U = PS_TILE_QUADS_PER_LANE;
+  const unsigned long long at = ((unsigned long long)first_tile + blockIdx.x) * PS_TILE_ELEMS;
+  const uint32_t tid = threadIdx.x;
+  f32x4 acc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  for (uint32_t s0 = 0; s0 < streams; s0 += 2) {
+    f32x4 x[2][U];
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const uint32_t sidx = s0 + g < streams ? s0 + g : s0;   // an odd count reads its last array twice
+      const __amdgpu_buffer_rsrc_t r = span(base + sidx * stride + at, PS_TILE_ELEMS * 4);
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[g][u] = load4(r, (u * PS_WG + tid) * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc[u] = acc[u] + x[g][u];
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  f32x4 t = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  if (t[0] + t[1] + t[2] + t[3] == 1.2345678e-29f) base[at + tid] = t[0];
 }
 
 // Zero n floats at p (16-byte aligned): a job's shards at registration.
@@ -488,14 +534,72 @@ void ps_static_scratch_unlock(PsStaticScratch* s) {
   static_cast<std::mutex*>(s->use_mutex)->unlock();
 }
 
+uint32_t ps_resident_copy_workgroups() {
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0 ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ps_copy_shards, PS_WG, 0) != hipSuccess || per_cu <= 0)
+    return 0;
+  return (uint32_t)(per_cu * cus);
+}
+
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
-                   void* stream_) {
+                   void* stream_, uint32_t launch_tiles, double hold_ticks_per_tile) {
   if (n == 0) return 0;
   const uint64_t tiles = (n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
   if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
-  hipLaunchKernelGGL(ps_copy_shards, dim3((uint32_t)tiles), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_),
-                     src_p, dst_p, src_v, dst_v, (unsigned long long)n);
-  return (int)hipGetLastError();
+  const bool resident_known = launch_tiles != 0;
+  if (!resident_known) launch_tiles = 0x7FFFFFFFu;   // one launch, and no hold: later generations would wait again
+  (void)hipGetLastError();
+  for (uint64_t t = 0; t < tiles; t += launch_tiles) {
+    const uint32_t m = (uint32_t)std::min<uint64_t>(launch_tiles, tiles - t);
+    // never longer than half a millisecond at the clock's nominal 100 MHz
+    const uint32_t hold = resident_known ? (uint32_t)std::min(hold_ticks_per_tile * m, 5.0e4) : 0u;
+    hipLaunchKernelGGL(ps_copy_shards, dim3(m), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_),
+                       src_p, dst_p, src_v, dst_v, (unsigned long long)n, (uint32_t)t, hold);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+  }
+  return 0;
+}
+
+int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_per_sec) {
+  *out_bytes_per_sec = 0.0;
+  constexpr uint32_t kStreams = 10;   // eight workers' gradients, parameters, momentum
+  constexpr int kLaunchesMax = 9;     // the first is not timed
+  const uint32_t resident = ps_resident_workgroups(8);
+  if (!arena || resident == 0) return -1;
+  const uint64_t stride = arena_bytes / 4 / kStreams / PS_TILE_ELEMS * PS_TILE_ELEMS;   // floats, whole tiles
+  const uint64_t tiles_per_stream = stride / PS_TILE_ELEMS;
+  const int launches = (int)std::min<uint64_t>(kLaunchesMax, tiles_per_stream / resident);
+  if (launches < 4) return -1;        // too small to read fresh memory in every launch
+  hipStream_t st = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  float ms = 0.0f;
+  if (e == hipSuccess) {
+    (void)hipGetLastError();
+    for (int l = 0; l < launches && e == hipSuccess; ++l) {
+      if (l == 1) e = hipEventRecord(e0, st);
+      if (e != hipSuccess) break;
+      hipLaunchKernelGGL(ps_probe_read, dim3(resident), dim3(PS_WG), 0, st, static_cast<float*>(arena),
+                         (unsigned long long)stride, kStreams, (uint32_t)l * resident);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  }
+  if (e1) (void)hipEventDestroy(e1);
+  if (e0) (void)hipEventDestroy(e0);
+  if (st) (void)hipStreamDestroy(st);
+  if (e != hipSuccess) return (int)e;
+  if (!(ms > 0.0f)) return -1;
+  const double bytes = (double)(launches - 1) * resident * PS_TILE_ELEMS * 4.0 * kStreams;
+  *out_bytes_per_sec = bytes / (ms * 1.0e-3);
+  return 0;
 }
 
 int ps_launch_zero(float* p, uint64_t n, void* stream_) {

@@ -132,9 +132,47 @@ struct ps_ctx {
   std::vector<Arrival*> arrivals;       // every arrival event ever created (owned)
   std::vector<Arrival*> arrivals_free;  // those no block refers to
   uint32_t resident_tiles[PS_MAX_W + 1] = {};  // per W: workgroups the chip holds at once (0 = unknown)
+  uint32_t copy_resident = 0;    // the same for the migration copy kernel
+  double read_rate = PS_READ_BYTES_PER_SEC;    // bytes/s a launch's read phase sustains (measured if possible)
+  double write_rate = PS_WRITE_BYTES_PER_SEC;  // bytes/s of its write phase
+  bool calibrated = false;
 };
 
 namespace {
+
+// How fast this GPU's HBM is relative to the MI355X the built-in rates were
+// fitted on is a property of the device, not of a context: the first context on
+// a device whose arena is large enough measures it, later ones reuse it.
+constexpr int kMaxDevices = 64;
+std::mutex g_speed_mu;
+double g_speed[kMaxDevices] = {};   // 0 = not measured yet
+
+void calibrate_rates(ps_ctx* c, int dev) {
+  if (c->cfg.flags & PS_FLAG_NO_CALIBRATION) return;
+  if (dev < 0 || dev >= kMaxDevices) return;
+  double speed = 0.0;
+  {
+    std::lock_guard<std::mutex> g(g_speed_mu);
+    if (g_speed[dev] == 0.0) {
+      // median of five readings of the read probe (single readings scatter by about 2 %)
+      double r[5];
+      int got = 0;
+      for (; got < 5; ++got)
+        if (ps_measure_read_rate(c->cfg.arena_dev, c->cfg.arena_bytes, &r[got]) != 0) break;
+      if (got == 5) {
+        std::sort(r, r + 5);
+        // a reading far from an MI355X's is not believed: the built-in rates stand
+        const double rel = r[2] / PS_PROBE_NOMINAL_BYTES_PER_SEC;
+        if (rel >= 0.8 && rel <= 1.15) g_speed[dev] = rel;
+      }
+    }
+    speed = g_speed[dev];
+  }
+  if (speed == 0.0) return;
+  c->read_rate = PS_READ_BYTES_PER_SEC * speed;
+  c->write_rate = PS_WRITE_BYTES_PER_SEC * speed;
+  c->calibrated = true;
+}
 
 int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (!in) return PS_ERR_ARG;
@@ -144,7 +182,7 @@ int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (out->max_block_bytes % PS_ALIGN_BYTES != 0) return PS_ERR_ARG;
   if (out->max_block_bytes > (1ull << 30)) return PS_ERR_ARG;  // byte offsets inside a block are 32-bit
   if (out->small_block_elems > PS_SMALL_MAX_ELEMS) return PS_ERR_ARG;
-  if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
+  if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT | PS_FLAG_NO_CALIBRATION)) return PS_ERR_ARG;
   if (out->store_hold_permille > 2000) return PS_ERR_ARG;
   if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
   return PS_OK;
@@ -362,7 +400,7 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
     const bool fits = resident == 0 || ch.end - ch.begin <= resident;
     // never longer than half a millisecond, whatever the tables say: a resident
     // launch reads for far less, and every wave must leave its wait soon
-    const double ticks = frac * (double)ch.read_bytes / PS_READ_BYTES_PER_SEC * c->clock_hz;
+    const double ticks = frac * (double)ch.read_bytes / c->read_rate * c->clock_hz;
     ch.hold_ticks = fits ? (uint32_t)std::min(ticks, 5.0e-4 * c->clock_hz) : 0u;
   }
 
@@ -371,8 +409,7 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   double est = PS_EST_WAVE_SECONDS;
   for (const PsChunk& ch : P.chunks) {
     const double params = (double)ch.read_bytes / (4.0 * ch.W + 8.0);
-    est += (double)ch.read_bytes / PS_READ_BYTES_PER_SEC + 8.0 * params / PS_WRITE_BYTES_PER_SEC +
-           PS_EST_LAUNCH_SECONDS;
+    est += (double)ch.read_bytes / c->read_rate + 8.0 * params / c->write_rate + PS_EST_LAUNCH_SECONDS;
   }
   if (P.chunks.empty() && !P.bins.empty()) est += PS_EST_LAUNCH_SECONDS;
   P.stats.est_seconds = n > 0 ? est : 0.0;
@@ -381,6 +418,16 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
   P.stats.n_small_bins = (int64_t)P.bins.size();
   P.stats.n_launches = (int64_t)std::max<size_t>(P.chunks.size(), P.bins.empty() ? 0 : 1);
+}
+
+// Wall-clock ticks a copy launch holds its data per tile it moves: the tile's
+// bytes read (parameters and momentum) at the pure-read rate, scaled.
+double copy_hold_ticks_per_tile(const ps_ctx* c) {
+  const int32_t pm = c->cfg.store_hold_permille;
+  if (pm < 0) return 0.0;
+  // the caller's knob scales the copy's hold in the same proportion as the aggregation's
+  const double frac = PS_COPY_HOLD_PERMILLE / 1000.0 * (pm == 0 ? 1.0 : (double)pm / PS_DEFAULT_HOLD_PERMILLE);
+  return frac * (double)PS_TILE_ELEMS * 8.0 / c->read_rate * c->clock_hz;
 }
 
 // Wait for the wave that last used the slot.
@@ -545,6 +592,8 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) try {
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
       c->clock_hz = 1000.0 * khz;
     for (uint32_t w = 0; w <= PS_MAX_W; ++w) c->resident_tiles[w] = ps_resident_workgroups(w);
+    c->copy_resident = ps_resident_copy_workgroups();
+    calibrate_rates(c, dev);
     // everything ps_aggregate_noalloc will need, so that it never allocates:
     // this GPU's static array and a pinned staging buffer of the same size
     if (ps_static_scratch(&c->sscratch) != 0 ||
@@ -880,7 +929,8 @@ int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* ds
   }
   {
     const int le = ps_launch_copy(js->p + bs.flat_off, jd->p + bd.flat_off, js->v + bs.flat_off,
-                                  jd->v + bd.flat_off, (uint64_t)bs.numel, stream);
+                                  jd->v + bd.flat_off, (uint64_t)bs.numel, stream, src->copy_resident,
+                                  copy_hold_ticks_per_tile(src));
     if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
   }
   Arrival* a = arrival_get(dst);
@@ -946,7 +996,8 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
     const Block& last = js->blocks[ids[z]];
     const size_t bytes = (size_t)(last.flat_off + last.numel - first.flat_off) * 4;
     const int le = ps_launch_copy(js->p + first.flat_off, jd->p + first.flat_off, js->v + first.flat_off,
-                                  jd->v + first.flat_off, bytes / 4, stream);
+                                  jd->v + first.flat_off, bytes / 4, stream, src->copy_resident,
+                                  copy_hold_ticks_per_tile(src));
     if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
     a = z + 1;
   }
@@ -1208,6 +1259,16 @@ int32_t ps_pull_flat(ps_ctx* c, ps_job_t job, const float** out_param_dev, const
   if (out_param_dev) *out_param_dev = j->p;
   if (out_mom_dev) *out_mom_dev = j->v;
   if (out_flat_numel) *out_flat_numel = j->flat_numel;
+  return PS_OK;
+} PS_NO_THROW
+
+int32_t ps_rates(ps_ctx* c, ps_rates_info* out) try {
+  if (!c || !out) return PS_ERR_ARG;
+  std::lock_guard<std::mutex> g(c->mu);
+  out->read_bytes_per_sec = c->read_rate;
+  out->write_bytes_per_sec = c->write_rate;
+  out->calibrated = c->calibrated ? 1 : 0;
+  out->reserved_ = 0;
   return PS_OK;
 } PS_NO_THROW
 
