@@ -245,7 +245,8 @@ def measure(workload: str, args, keep: bool):
 
     specs, seed = specs_for(workload)
     t_setup = time.perf_counter()
-    gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
+    gpu = GpuService(specs, seed, flags=2 if args.no_calibration else 0,   # PS_FLAG_NO_CALIBRATION
+                     small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
                      store_hold_permille=args.hold_permille)
     gpu.fill_grads(0)
     torch.cuda.synchronize()
@@ -324,7 +325,8 @@ def measure(workload: str, args, keep: bool):
         "roofline": {
             "bound": "hbm", "kernel": "ps_agg_wave", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": measured_traffic(workload, not (args.small_elems or args.launch_tiles or args.hold_permille)),
+            "traffic": measured_traffic(workload, not (args.small_elems or args.launch_tiles or args.hold_permille
+                                                       or args.no_calibration)),
             "kernel_hash": kernel_hash(),
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_launch_ms,
             "launches": tm.n_launches, "launches_per_wave": stats.n_launches,
@@ -375,6 +377,8 @@ def main() -> int:
                     help="instead: time moving every block of --workload's first job to a second context")
     ap.add_argument("--migration-batched", action="store_true",
                     help="with --migration: only the one-call move of the whole job (for kernel profiles)")
+    ap.add_argument("--no-calibration", action="store_true",
+                    help="the library keeps its built-in HBM rates instead of measuring this GPU's")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
     ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")

@@ -104,7 +104,7 @@ typedef struct ps_config {
                                  store them only once this fraction (in 1/1000) of the
                                  launch's predicted read time has passed since they
                                  started, so that reads and writes reach HBM in separate
-                                 bursts; 0 = default (950), negative = no hold, at most 2000 */
+                                 bursts; 0 = default (960), negative = no hold, at most 2000 */
 } ps_config;
 
 typedef struct ps_block_ref {
@@ -393,7 +393,7 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
  * (the service's server profiler, Section 3.1: how fast this Aggregator is).
  * The built-in figures were fitted on MI355X.  ps_create measures, once per GPU
  * and process, how this GPU compares: a few read-only launches over the arena
- * before anything lives in it (median of five readings, about 3 ms in all),
+ * before anything lives in it (best of six readings, about 3 ms in all),
  * when the arena is at least about 1.4 GB; both rates are scaled by that
  * reading relative to the reference MI355X's.  With a smaller arena and no
  * earlier measurement in the process, with a reading outside 0.8 .. 1.15 of

@@ -95,16 +95,17 @@ inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e
 // a fixed cost): they predict when a launch's reads end, and how long a wave
 // takes (ps_wave_stats.est_seconds).  A workgroup starts to store when
 // PS_DEFAULT_HOLD_PERMILLE / 1000 of its launch's predicted read time has
-// passed: a little before the last reads are in, measured best at 950 for every
-// worker count (sweep on W = 2, 4, 8, 16: 910..985 within 1 %, 1000 1-2 %
-// slower, 1050 5 % slower).
+// passed: a little before the last reads are in.  Measured on uniform jobs with
+// W = 2, 4, 8, 16: 910..985 within 1 % of the best, 1050 5 % slower, 1100 10 %;
+// on a GPU whose read probe runs 3 % slower the best point sits 3-4 % later,
+// which is what the scaling of the rates by the probe's reading accounts for.
 constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
-constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 950;
+constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 960;
 constexpr double PS_WRITE_BYTES_PER_SEC = 6.0e12;
-// What ps_measure_read_rate reads on the MI355X boxes those rates were fitted on
-// (its launches include their fixed cost, so it reads lower than READ).  A
-// context scales both rates by (its GPU's reading / this).
-constexpr double PS_PROBE_NOMINAL_BYTES_PER_SEC = 6.78e12;
+// What ps_measure_read_rate reads at best on the MI355X those rates were fitted
+// on (its launches include their fixed cost, so it reads lower than READ).  A
+// context scales both rates by (its GPU's best reading / this).
+constexpr double PS_PROBE_NOMINAL_BYTES_PER_SEC = 6.88e12;
 constexpr double PS_EST_LAUNCH_SECONDS = 1.5e-6;
 // A copy's launches write as much as they read; measured on MI355X they are
 // fastest when the stores start at 900/1000 of the predicted read time (800:

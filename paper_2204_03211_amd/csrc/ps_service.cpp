@@ -154,15 +154,18 @@ void calibrate_rates(ps_ctx* c, int dev) {
   {
     std::lock_guard<std::mutex> g(g_speed_mu);
     if (g_speed[dev] == 0.0) {
-      // median of five readings of the read probe (single readings scatter by about 2 %)
-      double r[5];
+      // the best of six readings of the read probe: single readings scatter by
+      // about 2 %, always downwards (clocks still ramping, other traffic)
+      double best = 0.0;
       int got = 0;
-      for (; got < 5; ++got)
-        if (ps_measure_read_rate(c->cfg.arena_dev, c->cfg.arena_bytes, &r[got]) != 0) break;
-      if (got == 5) {
-        std::sort(r, r + 5);
+      for (; got < 6; ++got) {
+        double r = 0.0;
+        if (ps_measure_read_rate(c->cfg.arena_dev, c->cfg.arena_bytes, &r) != 0) break;
+        best = std::max(best, r);
+      }
+      if (got == 6) {
         // a reading far from an MI355X's is not believed: the built-in rates stand
-        const double rel = r[2] / PS_PROBE_NOMINAL_BYTES_PER_SEC;
+        const double rel = best / PS_PROBE_NOMINAL_BYTES_PER_SEC;
         if (rel >= 0.8 && rel <= 1.15) g_speed[dev] = rel;
       }
     }
