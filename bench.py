@@ -377,6 +377,9 @@ def main() -> int:
                     help="instead: time moving every block of --workload's first job to a second context")
     ap.add_argument("--migration-batched", action="store_true",
                     help="with --migration: only the one-call move of the whole job (for kernel profiles)")
+    ap.add_argument("--path-split-only", action="store_true",
+                    help="instead: only waves holding the small-path blocks alone, then the large-path blocks "
+                         "alone, --steps of each (for kernel profiles of the two paths)")
     ap.add_argument("--no-calibration", action="store_true",
                     help="the library keeps its built-in HBM rates instead of measuring this GPU's")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
@@ -408,6 +411,24 @@ def main() -> int:
     specs, seed = specs_for(args.workload)
     if args.migration:
         print(json.dumps(migration_bench(specs[0], args.steps, args.migration_batched)))
+        return 0
+    if args.path_split_only:
+        from harness import GpuService
+        gpu = GpuService(specs, seed, small_block_elems=args.small_elems)
+        gpu.fill_grads(0)
+        torch.cuda.synchronize()
+        gpu.push_all()
+        st = gpu.svc.plan_wave(gpu.wave())
+        gpu.svc.aggregate(gpu.wave())
+        res = _path_split(gpu.svc, gpu, specs, args.steps)
+        print(json.dumps({"path_split": True, "workload": args.workload, "waves_each": args.steps,
+                          "small_path": {"blocks": st.n_small_blocks, "bins": st.n_small_bins,
+                                         "params": st.small_params,
+                                         "algorithmic_bytes": st.small_algorithmic_bytes, **res["small"]},
+                          "large_path": {"blocks": st.n_blocks - st.n_small_blocks, "tiles": st.n_large_tiles,
+                                         "algorithmic_bytes": st.algorithmic_bytes - st.small_algorithmic_bytes,
+                                         **res["large"]}}))
+        gpu.close()
         return 0
     out, gpu, wave = measure(args.workload, args, keep=True)
     if args.workload == "packed_wave" and not args.no_side_configs:

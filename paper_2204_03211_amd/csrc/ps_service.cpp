@@ -355,13 +355,18 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
 
   // launch order of the large path.  Blocks are independent, so any
   // order gives the same result; tiles of one worker count are made adjacent
-  // (most workers first) and, inside a class, one job's blocks stay together,
-  // which keeps the number of HBM streams touched at any moment small.
+  // (most workers first); inside a class, one job's blocks stay together, which
+  // keeps the number of HBM streams touched at any moment small; and a job's
+  // blocks go in ascending address order, so that the workgroups of a launch,
+  // which start in index order, sweep every array upwards through one
+  // contiguous range (measured: the arrival order, last layer first, costs
+  // 1.4 % at W = 2 when layers are not whole launches, a random order 5 %).
   std::stable_sort(P.large_order.begin(), P.large_order.end(), [&](uint32_t a, uint32_t b) {
     const Job& ja = c->jobs[list[a].job];
     const Job& jb = c->jobs[list[b].job];
     if (ja.W != jb.W) return ja.W > jb.W;
-    return list[a].job < list[b].job;
+    if (list[a].job != list[b].job) return list[a].job < list[b].job;
+    return ja.blocks[list[a].block].flat_off < jb.blocks[list[b].block].flat_off;
   });
   uint32_t cur_w = 0;
   PsChunk chunk{0, 0, 0, 0, 0};
