@@ -1,7 +1,15 @@
 // Assignment and scaling of model aggregations (host only): cyclic execution,
-// the assignment heuristic, late requests, recycling on job exit, cluster best
-// fit -- the paper's Section 3.3.  Jobs and tasks are kept in flat vectors; an
-// Aggregator holds, per job in ascending id, that job's tasks in arrival order.
+// the assignment heuristic, late requests, recycling on job exit, scaling up on
+// arrival -- the paper's Section 3.3.
+//
+// Bookkeeping.  Every Aggregator keeps a ledger: per job it serves (ascending
+// id), that job's tasks in arrival order and the running sum of their execution
+// times, plus the Aggregator's cycle (the largest profiled iteration among its
+// jobs).  An estimate for a new task then costs one pass over the jobs of an
+// Aggregator, not over its tasks: a job brings thousands of tasks, an
+// Aggregator serves a handful of jobs.  Sums are always formed left to right
+// in arrival order (a removal recomputes the job's sum from its remaining
+// tasks), so every figure is reproducible to the last bit.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -22,13 +30,22 @@ struct Task {
   bool live = false;
 };
 
-struct Agg {
-  bool live = false;
-  std::map<int32_t, std::vector<int32_t>> by_job;  // job -> task ids, arrival order
+// One job's share of one Aggregator.
+struct Share {
+  std::vector<int32_t> tasks;  // arrival order
+  double e_sum = 0.0;          // their execution times added in that order
 };
 
-double stretched(double C, double D) { return std::max(D, C / std::floor(C / D)); }
-double lost(double d, double D) { return (d - D) / d; }
+struct Ledger {
+  bool live = false;
+  std::map<int32_t, Share> share;  // job -> its share, ascending job id
+  double cycle = 0.0;              // C_n: max profiled iteration of the jobs here, 0 if none
+};
+
+// d_j of a job with profiled iteration D under cycle C, and the loss that goes with it
+inline double runs_per_cycle(double C, double D) { return std::floor(C / D); }
+inline double iteration_under(double C, double D) { return std::max(D, C / runs_per_cycle(C, D)); }
+inline double speed_loss(double d, double D) { return (d - D) / d; }
 
 }  // namespace
 
@@ -36,56 +53,69 @@ struct ps_sched {
   double limit = PS_SCHED_DEFAULT_LOSS_LIMIT;
   std::vector<double> D;        // per job; <= 0 once the job has left
   std::vector<Task> tasks;
-  std::vector<Agg> aggs;
+  std::vector<Ledger> aggs;
   std::map<int32_t, std::vector<int32_t>> own;  // job -> Aggregators added for it by scale-up, oldest first
 
   bool job_ok(int32_t j) const { return j >= 0 && (size_t)j < D.size() && D[j] > 0; }
   bool agg_ok(int32_t n) const { return n >= 0 && (size_t)n < aggs.size() && aggs[n].live; }
+  bool empty(int32_t n) const { return aggs[n].share.empty(); }
+  double cycle(int32_t n) const { return aggs[n].cycle; }
 
-  double cycle(int32_t n) const {
-    double c = 0.0;
-    for (const auto& kv : aggs[n].by_job) c = std::max(c, D[kv.first]);
-    return c;
+  // --- ledger operations ---------------------------------------------------
+  void ledger_add(int32_t n, int32_t t) {
+    Ledger& a = aggs[n];
+    Share& sh = a.share[tasks[t].job];
+    sh.tasks.push_back(t);
+    sh.e_sum += tasks[t].e;
+    a.cycle = std::max(a.cycle, D[tasks[t].job]);
   }
+  void ledger_remove(int32_t n, int32_t t) {
+    Ledger& a = aggs[n];
+    auto it = a.share.find(tasks[t].job);
+    Share& sh = it->second;
+    sh.tasks.erase(std::find(sh.tasks.begin(), sh.tasks.end(), t));
+    if (sh.tasks.empty()) {
+      a.share.erase(it);
+      a.cycle = 0.0;
+      for (const auto& kv : a.share) a.cycle = std::max(a.cycle, D[kv.first]);
+    } else {
+      sh.e_sum = 0.0;
+      for (int32_t q : sh.tasks) sh.e_sum += tasks[q].e;
+    }
+  }
+  void ledger_drop_job(int32_t n, int32_t job) {
+    Ledger& a = aggs[n];
+    a.share.erase(job);
+    a.cycle = 0.0;
+    for (const auto& kv : a.share) a.cycle = std::max(a.cycle, D[kv.first]);
+  }
+
+  // W_n: aggregation time within one cycle of length C
   double busy(int32_t n, double C) const {
     double total = 0.0;
-    for (const auto& kv : aggs[n].by_job) {
-      const double d = stretched(C, D[kv.first]);
-      double sum = 0.0;
-      for (int32_t t : kv.second) sum += tasks[t].e;
-      total += std::floor(C / d) * sum;
-    }
+    for (const auto& kv : aggs[n].share)
+      total += runs_per_cycle(C, iteration_under(C, D[kv.first])) * kv.second.e_sum;
     return total;
   }
-  // Pseudocode 1, first loop body.  Returns false if the loss limit rejects n.
+
+  // The first half of the assignment scheme for one Aggregator and a task of
+  // job k: the cycle if k joined, whether anybody (k included) would lose the
+  // limit or more, and the free time left.
   bool estimate(int32_t n, int32_t k, double* C_est, double* F_est) const {
-    const double C = std::max(cycle(n), D[k]);
-    bool k_seen = false;
-    for (const auto& kv : aggs[n].by_job) {
-      if (kv.first == k) k_seen = true;
-      if (lost(stretched(C, D[kv.first]), D[kv.first]) >= limit) return false;
-    }
-    if (!k_seen && lost(stretched(C, D[k]), D[k]) >= limit) return false;
+    const Ledger& a = aggs[n];
+    const double C = std::max(a.cycle, D[k]);
+    for (const auto& kv : a.share)
+      if (speed_loss(iteration_under(C, D[kv.first]), D[kv.first]) >= limit) return false;
+    if (!a.share.count(k) && speed_loss(iteration_under(C, D[k]), D[k]) >= limit) return false;
     *C_est = C;
     *F_est = C - busy(n, C);
     return true;
   }
+
   int32_t allocate() {
     aggs.emplace_back();
     aggs.back().live = true;
     return (int32_t)aggs.size() - 1;
-  }
-  // Best-fit destination, or -1.
-  int32_t choose(int32_t k, double e, int32_t exclude) const {
-    int32_t best = -1;
-    double best_f = 0.0;
-    for (int32_t n = 0; n < (int32_t)aggs.size(); ++n) {
-      if (!aggs[n].live || n == exclude) continue;
-      double C, F;
-      if (!estimate(n, k, &C, &F)) continue;
-      if (F >= e && (best < 0 || F < best_f)) { best = n; best_f = F; }
-    }
-    return best;
   }
   // Hand an Aggregator back; no job keeps it as one of its own.
   void release(int32_t n) {
@@ -96,54 +126,55 @@ struct ps_sched {
       it = v.empty() ? own.erase(it) : std::next(it);
     }
   }
-  int32_t choose_excluding(int32_t k, double e, const std::vector<int32_t>& skip) const {
+
+  // The second half: among the live Aggregators not in `skip` that qualify and
+  // have room for e, the one with the least free time (first such id on ties);
+  // -1 if none.
+  int32_t best_fit(int32_t k, double e, const int32_t* skip, size_t n_skip) const {
     int32_t best = -1;
     double best_f = 0.0;
     for (int32_t n = 0; n < (int32_t)aggs.size(); ++n) {
-      if (!aggs[n].live || std::find(skip.begin(), skip.end(), n) != skip.end()) continue;
+      if (!aggs[n].live || std::find(skip, skip + n_skip, n) != skip + n_skip) continue;
       double C, F;
-      if (!estimate(n, k, &C, &F)) continue;
-      if (F >= e && (best < 0 || F < best_f)) { best = n; best_f = F; }
+      if (!estimate(n, k, &C, &F) || F < e) continue;
+      if (best < 0 || F < best_f) { best = n; best_f = F; }
     }
     return best;
   }
+
   void place(int32_t n, int32_t t) {
     tasks[t].agg = n;
-    aggs[n].by_job[tasks[t].job].push_back(t);
+    ledger_add(n, t);
   }
-  void unplace(int32_t t) {
-    auto& a = aggs[tasks[t].agg];
-    auto it = a.by_job.find(tasks[t].job);
-    auto& v = it->second;
-    v.erase(std::find(v.begin(), v.end(), t));
-    if (v.empty()) a.by_job.erase(it);
-  }
+  void unplace(int32_t t) { ledger_remove(tasks[t].agg, t); }
+
+  // Recycling: every task of the victim must find room elsewhere, largest
+  // first, with no allocation.  The victim's own ledger is left as it is while
+  // destinations are tried (it is not a destination), so a failed attempt only
+  // has to take the tentative entries out of the destinations again.
   bool drain(int32_t victim) {
     std::vector<int32_t> todo;
-    for (const auto& kv : aggs[victim].by_job) todo.insert(todo.end(), kv.second.begin(), kv.second.end());
+    for (const auto& kv : aggs[victim].share) todo.insert(todo.end(), kv.second.tasks.begin(), kv.second.tasks.end());
     std::sort(todo.begin(), todo.end(), [&](int32_t a, int32_t b) {
       if (tasks[a].e != tasks[b].e) return tasks[a].e > tasks[b].e;
       return a < b;
     });
-    // tasks stay listed on the victim while copies are tried elsewhere
-    std::vector<int32_t> moved;
+    std::vector<int32_t> tentative;
     for (int32_t t : todo) {
-      const int32_t n = choose(tasks[t].job, tasks[t].e, victim);
+      const int32_t n = best_fit(tasks[t].job, tasks[t].e, &victim, 1);
       if (n < 0) {
-        for (int32_t m : moved) {  // roll back
-          auto& a = aggs[tasks[m].agg];
-          auto it = a.by_job.find(tasks[m].job);
-          it->second.erase(std::find(it->second.begin(), it->second.end(), m));
-          if (it->second.empty()) a.by_job.erase(it);
+        for (int32_t m : tentative) {
+          ledger_remove(tasks[m].agg, m);
           tasks[m].agg = victim;
         }
         return false;
       }
-      aggs[n].by_job[tasks[t].job].push_back(t);
+      ledger_add(n, t);
       tasks[t].agg = n;
-      moved.push_back(t);
+      tentative.push_back(t);
     }
-    aggs[victim].by_job.clear();
+    aggs[victim].share.clear();
+    aggs[victim].cycle = 0.0;
     return true;
   }
 };
@@ -176,7 +207,7 @@ int32_t ps_sched_add_job(ps_sched* s, double D, int32_t* out_job) try {
 int32_t ps_sched_assign(ps_sched* s, int32_t job, double e, int32_t* out_task, int32_t* out_aggregator) try {
   if (!s || !(e > 0) || !std::isfinite(e)) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
-  int32_t n = s->choose(job, e, -1);
+  int32_t n = s->best_fit(job, e, nullptr, 0);
   if (n < 0) n = s->allocate();
   Task t;
   t.job = job; t.e = e; t.live = true;
@@ -203,17 +234,17 @@ int32_t ps_sched_remove_job(ps_sched* s, int32_t job, int32_t* out_released, int
   if (!s || cap < 0 || (cap > 0 && !out_released)) return PS_ERR_ARG;
   if (!s->job_ok(job)) return PS_ERR_BAD_JOB;
   std::vector<int32_t> released;
-  for (auto& a : s->aggs) {
-    if (!a.live) continue;
-    auto it = a.by_job.find(job);
-    if (it == a.by_job.end()) continue;
-    for (int32_t t : it->second) s->tasks[t].live = false;
-    a.by_job.erase(it);
+  for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n) {
+    if (!s->aggs[n].live) continue;
+    auto it = s->aggs[n].share.find(job);
+    if (it == s->aggs[n].share.end()) continue;
+    for (int32_t t : it->second.tasks) s->tasks[t].live = false;
+    s->ledger_drop_job(n, job);
   }
   s->D[job] = -1.0;
   s->own.erase(job);
   for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n)
-    if (s->aggs[n].live && s->aggs[n].by_job.empty()) {
+    if (s->aggs[n].live && s->empty(n)) {
       s->release(n);
       released.push_back(n);
     }
@@ -256,12 +287,12 @@ int32_t ps_sched_scale_up_job(ps_sched* s, int32_t job, int32_t* out_new_aggrega
       double C, F;
       if (s->estimate(cand, job, &C, &F) && F >= e) { n = cand; break; }
     }
-    if (n < 0) n = s->choose_excluding(job, e, s->own[job]);
+    if (n < 0) n = s->best_fit(job, e, s->own[job].data(), s->own[job].size());
     if (n < 0) n = s->allocate();
     s->place(n, t);
   }
   for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n)
-    if (s->aggs[n].live && s->aggs[n].by_job.empty()) s->release(n);
+    if (s->aggs[n].live && s->empty(n)) s->release(n);
   int32_t moved = 0;
   for (size_t i = 0; i < mine.size(); ++i) moved += s->tasks[mine[i]].agg != before[i] ? 1 : 0;
   if (out_new_aggregator) *out_new_aggregator = fresh;
@@ -276,9 +307,9 @@ int32_t ps_sched_aggregator_info(ps_sched* s, int32_t aggregator, ps_sched_agg_s
   out->cycle = C;
   out->busy = C > 0 ? s->busy(aggregator, C) : 0.0;
   out->free_time = C - out->busy;
-  out->n_jobs = (int32_t)s->aggs[aggregator].by_job.size();
+  out->n_jobs = (int32_t)s->aggs[aggregator].share.size();
   out->n_tasks = 0;
-  for (const auto& kv : s->aggs[aggregator].by_job) out->n_tasks += (int32_t)kv.second.size();
+  for (const auto& kv : s->aggs[aggregator].share) out->n_tasks += (int32_t)kv.second.tasks.size();
   return PS_OK;
 } PS_NO_THROW
 
@@ -292,17 +323,17 @@ int32_t ps_sched_job_info(ps_sched* s, int32_t job, ps_sched_job_stats* out) try
   out->n_aggregators = 0;
   for (int32_t n = 0; n < (int32_t)s->aggs.size(); ++n) {
     if (!s->aggs[n].live) continue;
-    auto it = s->aggs[n].by_job.find(job);
-    if (it == s->aggs[n].by_job.end()) continue;
-    const double dn = stretched(s->cycle(n), D);
+    auto it = s->aggs[n].share.find(job);
+    if (it == s->aggs[n].share.end()) continue;
+    const double dn = iteration_under(s->cycle(n), D);
     d = any ? std::max(d, dn) : dn;
     any = true;
-    out->n_tasks += (int32_t)it->second.size();
+    out->n_tasks += (int32_t)it->second.tasks.size();
     out->n_aggregators += 1;
   }
   out->D = D;
   out->d = d;
-  out->loss = lost(d, D);
+  out->loss = speed_loss(d, D);
   return PS_OK;
 } PS_NO_THROW
 
@@ -339,7 +370,7 @@ int32_t ps_sched_cycle_plan(ps_sched* s, int32_t aggregator, ps_sched_wave* out_
     bool operator<(const Key& o) const { return (__int128)num * o.den < (__int128)o.num * den; }
   };
   std::map<Key, std::vector<int32_t>> at;
-  for (const auto& kv : s->aggs[aggregator].by_job) {
+  for (const auto& kv : s->aggs[aggregator].share) {
     const int64_t r = (int64_t)std::floor(C / s->D[kv.first]);
     for (int64_t i = 0; i < r; ++i) {
       const int64_t g = std::gcd(i, r);

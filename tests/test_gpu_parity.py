@@ -737,6 +737,72 @@ def test_batched_migration_keeps_the_trajectory(orc):
         c.close()
 
 
+def test_migration_of_a_model_larger_than_one_copy_launch():
+    """ps_migrate_many of a job of 11 M parameters in ragged layers: the copy is
+    cut into several resident-size launches (2048 tiles each) with a store hold.
+    What arrives must be what was there, bit for bit, padding untouched, both
+    with the hold and without it."""
+    from paper_2204_03211_amd import ParameterService
+    dev = torch.device("cuda:0")
+    layers = [5_000_003, 4097, 6_100_001, 7]
+    for hold in (0, -1):
+        need = ParameterService.job_arena_bytes(layers) + 256
+        arenas = [torch.full((need,), 0x5A, dtype=torch.uint8, device=dev) for _ in range(2)]
+        a, b = ParameterService(arenas[0], store_hold_permille=hold), ParameterService(arenas[1], store_hold_permille=hold)
+        init = [layer_values(5, "param", (0, l), n, 0.05, dev) for l, n in enumerate(layers)]
+        ja, nb = a.register_job(layers, 2, 0.1, 0.9, 1e-4, init)
+        jb, _ = b.register_shadow_job(layers, 2, 0.1, 0.9, 1e-4)
+        pa, va = a.pull_flat(ja)
+        wl.fill_normal_like(va, wl.stream_key(5, "mom"), 0.01)       # momentum with content of its own
+        torch.cuda.synchronize()
+        want_p, want_v = pa.clone(), va.clone()
+        a.migrate_many(ja, list(range(nb)), b, jb)
+        torch.cuda.synchronize()
+        pb, vb = b.pull_flat(jb)
+        for blk in range(nb):
+            i = b.job_block_info(jb, blk)
+            sl = slice(i.flat_offset, i.flat_offset + i.numel)
+            assert torch.equal(pb[sl].view(torch.int32), want_p[sl].view(torch.int32)), (hold, blk)
+            assert torch.equal(vb[sl].view(torch.int32), want_v[sl].view(torch.int32)), (hold, blk)
+            assert b.pull(jb, blk).data_ptr() == pb[sl].data_ptr()
+        # nothing beyond the job's arrays was written in the receiving arena
+        used = 8 * b.job_flat_numel(jb)
+        assert (arenas[1][used:] == 0x5A).all()
+        a.close(); b.close()
+
+
+def test_read_rate_calibration_changes_timing_only(orc):
+    """ps_create measures the GPU's read rate when the arena is large enough, once
+    per process; a context can opt out.  The rates steer the store hold and the
+    predicted wave time, never a result."""
+    from paper_2204_03211_amd import ParameterService
+    from paper_2204_03211_amd.binding import FLAG_NO_CALIBRATION
+    dev = torch.device("cuda:0")
+    big = torch.empty(1_600_000_000, dtype=torch.uint8, device=dev)
+    first = ParameterService(big)
+    r = first.rates()
+    assert r.calibrated == 1 and 5.6e12 <= r.read_bytes_per_sec <= 8.05e12
+    assert r.write_bytes_per_sec == pytest.approx(r.read_bytes_per_sec * 6.0 / 7.0, rel=1e-12)
+    first.close()
+    del big
+    small = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    again = ParameterService(small)                      # too small to measure: the process's reading is reused
+    assert again.rates().calibrated == 1 and again.rates().read_bytes_per_sec == r.read_bytes_per_sec
+    again.close()
+    off = ParameterService(small, flags=FLAG_NO_CALIBRATION)
+    assert off.rates().calibrated == 0 and off.rates().read_bytes_per_sec == 7.0e12
+    off.close()
+    # same jobs with and without calibration: identical bits, both equal to the oracle
+    specs = [spec([300_000, 64, 4099], 8), spec([9000, 50_000], 2)]
+    cal, _ = run_both(orc, specs, seed=13, rounds=2)
+    nocal, _ = run_both(orc, specs, seed=13, rounds=2, flags=FLAG_NO_CALIBRATION)
+    assert cal.svc.rates().calibrated == 1 and nocal.svc.rates().calibrated == 0
+    for ji, s in enumerate(specs):
+        for l in range(len(s.layer_numel)):
+            assert torch.equal(cal.layer_param(ji, l), nocal.layer_param(ji, l))
+    cal.close(); nocal.close()
+
+
 def test_big_blocks_and_wide_jobs(orc):
     """A 16 MiB block cap (one 5 M-element block: offsets far beyond one launch),
     W = 32 on a multi-tile layer, and W = 1."""

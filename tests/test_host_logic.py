@@ -349,3 +349,10 @@ def test_pushes_from_many_threads():
     assert not errors
     assert all(svc.job_block_info(job, b).push_mask == (1 << W) - 1 for b in range(nb))
     assert svc.plan_wave(svc.pack_wave([job])).n_blocks == nb
+
+
+def test_rates_of_a_planning_context_are_the_built_in_ones():
+    svc = ParameterService(None)
+    r = svc.rates()
+    assert (r.read_bytes_per_sec, r.write_bytes_per_sec, r.calibrated) == (7.0e12, 6.0e12, 0)
+    svc.close()
