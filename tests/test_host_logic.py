@@ -356,3 +356,23 @@ def test_rates_of_a_planning_context_are_the_built_in_ones():
     r = svc.rates()
     assert (r.read_bytes_per_sec, r.write_bytes_per_sec, r.calibrated) == (7.0e12, 6.0e12, 0)
     svc.close()
+
+
+def test_noalloc_entry_point_validates_like_ps_aggregate_on_a_planning_context():
+    svc = ParameterService(None)
+    job, nb = reg(svc, [5000, 10], W=2)
+    wave = svc.pack_wave([job])
+    with pytest.raises(PsError) as ei:
+        svc.aggregate_noalloc(wave)
+    assert ei.value.name == "PS_ERR_NOT_READY"
+    for w in range(2):
+        svc.push_flat(job, w, FAKE)
+    with pytest.raises(PsError) as ei:
+        svc.aggregate_noalloc(WaveList(wave.tolist() + wave.tolist()[:1]))
+    assert ei.value.name == "PS_ERR_DUP_BLOCK"
+    with pytest.raises(PsError) as ei:
+        svc.aggregate_noalloc(wave)
+    assert ei.value.name == "PS_ERR_NO_DEVICE"          # valid list, but nothing to run it on
+    svc.aggregate_noalloc(WaveList([]))                  # empty list: no-op
+    assert svc.job_block_info(job, 0).round == 0 and svc.job_block_info(job, 0).push_mask == 3
+    svc.close()
