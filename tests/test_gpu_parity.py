@@ -516,7 +516,7 @@ def test_reused_tables_notice_a_block_that_came_back_with_another_round(orc):
         here.aggregate(wave)
         oracle_step(o.jobs[0].arrival(), r)
     torch.cuda.synchronize()
-    # one block goes away, advances a round there on round 2's gradients, and comes back
+    # one block goes away, is aggregated once there (with the gradients of training round index 2), and comes back
     here.migrate_begin(ja, away)
     here.migrate_copy(ja, away, there, jb)
     fill(2)
