@@ -115,8 +115,9 @@ def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
                       "note": "same oracle calls issued from a thread pool, one block per call"},
         "value": n_params / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
         "GB_per_s": n_bytes / dt / 1e9, "seconds": dt,
-        "sample": f"every {k}-th block of the wave list: {len(work)} of {len(wave_refs)} blocks, "
-                  f"{n_params} params, single-threaded C++ oracle on host memory",
+        "sample": (f"every block of the wave list" if k == 1 else f"every {k}-th block of the wave list")
+                  + f": {len(work)} of {len(wave_refs)} blocks, {n_params} params, "
+                    "single-threaded C++ oracle on host memory",
         "host_cpu": _cpu_model(), "host_cores_total": os.cpu_count(),
     }
 
