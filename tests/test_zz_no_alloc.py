@@ -104,3 +104,23 @@ def test_noalloc_refuses_a_wave_that_does_not_fit():
     assert svc.job_block_info(job, nb - 1).round == 1
     assert float(svc.pull(job, 5)[0]) == float(np.float32(-3.2))     # p = 0 - 0.1 * 32
     svc.close()
+
+
+def test_noalloc_on_the_full_packed_wave():
+    """The twelve-job wave at full size (1743 blocks, 219 631 tiles: 4.2 MB of the
+    8 MiB array) through the entry point that allocates nothing, two rounds (the
+    second reuses the tables in the array), against ps_aggregate on a twin
+    service with the same seeded inputs: every parameter, momentum value and
+    telemetry pair identical."""
+    specs = wl.packed_wave_jobs(42)
+    ref, alt = GpuService(specs, 42), GpuService(specs, 42)
+    wave_r, wave_a = ref.wave(), alt.wave()
+    assert wave_r.tolist() == wave_a.tolist() and len(wave_r) == 1743
+    for r in range(2):
+        for g in (ref, alt):
+            g.fill_grads(r)
+            g.push_all()
+        ref.svc.aggregate(wave_r)
+        alt.svc.aggregate_noalloc(wave_a)
+    assert_same(ref, alt, "full packed wave")
+    ref.close(); alt.close()
