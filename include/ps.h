@@ -169,8 +169,11 @@ typedef struct ps_timing {
 
 /* --- life cycle ---------------------------------------------------------- */
 
-/* Create a context.  cfg is copied.  No device memory is allocated here except
- * the library's own small tables, which grow on demand inside ps_aggregate.
+/* Create a context.  cfg is copied.  The library's own device tables are small
+ * and grow on demand inside ps_aggregate; ps_create itself allocates 8 MiB of
+ * pinned host memory (the staging buffer of ps_aggregate_noalloc) and, while it
+ * measures the GPU (see ps_rates), a stream, two events and 1 KB of device
+ * memory that it releases again.  The arena's contents are only read.
  * Errors: PS_ERR_ARG (bad cfg, misaligned arena, small_block_elems > 4096). */
 int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx);
 

@@ -154,11 +154,12 @@ uint32_t ps_resident_copy_workgroups();
 
 // Measure the rate at which launches shaped like the aggregation's read HBM:
 // a few launches of as many workgroups as the chip holds, each reading ten
-// arrays' tiles from the (still unused) arena, timed with events on a stream of
-// their own.  Synchronous.  Returns 0 and the rate, -1 if the arena is too
+// arrays' tiles from the arena and writing nothing to it, timed with events on
+// a stream of their own (which, with a 1 KB sink, is created and released
+// here).  Synchronous.  Returns 0 and the rate, -1 if the arena is too
 // small to give every launch fresh memory (about 1.4 GB are needed) or the
 // device cannot be queried, else a hipError_t value.
-int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_per_sec);
+int ps_measure_read_rate(const void* arena, uint64_t arena_bytes, double* out_bytes_per_sec);
 
 // Enqueue on stream the zeroing of n floats at p (16-byte aligned) with a fill
 // kernel (no memset node, so the call may sit inside a captured graph).

@@ -374,12 +374,13 @@ __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict_
 // Read-rate probe: the read phase of an aggregation launch and nothing else.
 // A workgroup reads one tile of each of `streams` arrays that lie `stride`
 // floats apart (two arrays' loads in flight together, as in tile_body), adds
-// everything up and stores nothing -- unless the sum hits one particular value,
-// which keeps the loads alive for the compiler; the arena it reads is not in
-// use yet, so even that store would do no harm.
+// everything up and stores nothing to the arrays it reads; should the sum hit
+// one particular value, it goes to `sink` (PS_WG floats of the probe's own),
+// which keeps the loads alive for the compiler.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(PS_WG) void ps_probe_read(float* __restrict__ base, unsigned long long stride,
-                                                       uint32_t streams, uint32_t first_tile) {
+__global__ __launch_bounds__(PS_WG) void ps_probe_read(const float* __restrict__ base, unsigned long long stride,
+                                                       uint32_t streams, uint32_t first_tile,
+                                                       float* __restrict__ sink) {
   constexpr int U = PS_TILE_QUADS_PER_LANE;
   const unsigned long long at = ((unsigned long long)first_tile + blockIdx.x) * PS_TILE_ELEMS;
   const uint32_t tid = threadIdx.x;
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(PS_WG) void ps_probe_read(float* __restrict__ base,
     __builtin_amdgcn_sched_barrier(0);
   }
   f32x4 t = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-  if (t[0] + t[1] + t[2] + t[3] == 1.2345678e-29f) base[at + tid] = t[0];
+  if (t[0] + t[1] + t[2] + t[3] == 1.2345678e-29f) sink[tid] = t[0];
 }
 
 // Zero n floats at p (16-byte aligned): a job's shards at registration.
@@ -563,7 +564,7 @@ int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* 
   return 0;
 }
 
-int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_per_sec) {
+int ps_measure_read_rate(const void* arena, uint64_t arena_bytes, double* out_bytes_per_sec) {
   *out_bytes_per_sec = 0.0;
   constexpr uint32_t kStreams = 10;   // eight workers' gradients, parameters, momentum
   constexpr int kLaunchesMax = 9;     // the first is not timed
@@ -575,7 +576,9 @@ int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_pe
   if (launches < 4) return -1;        // too small to read fresh memory in every launch
   hipStream_t st = nullptr;
   hipEvent_t e0 = nullptr, e1 = nullptr;
+  float* sink = nullptr;
   hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipMalloc((void**)&sink, PS_WG * sizeof(float));
   if (e == hipSuccess) e = hipEventCreate(&e0);
   if (e == hipSuccess) e = hipEventCreate(&e1);
   float ms = 0.0f;
@@ -584,14 +587,16 @@ int ps_measure_read_rate(void* arena, uint64_t arena_bytes, double* out_bytes_pe
     for (int l = 0; l < launches && e == hipSuccess; ++l) {
       if (l == 1) e = hipEventRecord(e0, st);
       if (e != hipSuccess) break;
-      hipLaunchKernelGGL(ps_probe_read, dim3(resident), dim3(PS_WG), 0, st, static_cast<float*>(arena),
-                         (unsigned long long)stride, kStreams, (uint32_t)l * resident);
+      hipLaunchKernelGGL(ps_probe_read, dim3(resident), dim3(PS_WG), 0, st, static_cast<const float*>(arena),
+                         (unsigned long long)stride, kStreams, (uint32_t)l * resident, sink);
       e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipEventRecord(e1, st);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
   }
+  if (st) (void)hipStreamSynchronize(st);   // nothing of the probe is still running when its memory goes
+  if (sink) (void)hipFree(sink);
   if (e1) (void)hipEventDestroy(e1);
   if (e0) (void)hipEventDestroy(e0);
   if (st) (void)hipStreamDestroy(st);

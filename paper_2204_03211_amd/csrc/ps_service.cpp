@@ -1179,6 +1179,21 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
     }
     return hip_fail(c, (hipError_t)le, "launching the wave");
   }
+  // the wave is enqueued: consume the pushes (before anything else can fail, so
+  // that a retry after an error below cannot apply them a second time)
+  for (int64_t i = 0; i < n; ++i) {
+    Job& j = c->jobs[list[i].job];
+    Block& b = j.blocks[list[i].block];
+    b.mask = 0;
+    b.round += 1;
+  }
+  s.plan.uses += 1;
+  if (ts) {
+    ts->pending = true;
+    ts->launches = s.plan.stats.n_launches;
+  }
+  // The tables stay trusted only once the event that guards them is recorded.
+  s.valid = false;
   if (noalloc) {
     PS_HIP(c, hipEventRecord(static_cast<hipEvent_t>(ss->last), hs));
     ss->in_flight = true;
@@ -1190,19 +1205,6 @@ static int32_t aggregate_impl(ps_ctx* c, const ps_block_ref* list, int64_t n, vo
     c->last_slot = (int)(sp - c->slots);
   }
   s.valid = true;
-  s.plan.uses += 1;
-  if (ts) {
-    ts->pending = true;
-    ts->launches = s.plan.stats.n_launches;
-  }
-
-  // the wave is enqueued: consume the pushes
-  for (int64_t i = 0; i < n; ++i) {
-    Job& j = c->jobs[list[i].job];
-    Block& b = j.blocks[list[i].block];
-    b.mask = 0;
-    b.round += 1;
-  }
   return PS_OK;
 }
 
