@@ -6,7 +6,9 @@
 #include <cstdio>
 #include <cstdlib>
 #include <algorithm>
+#include <cstring>
 #include <random>
+#include <thread>
 #include <vector>
 
 #include "../../include/ps.h"
@@ -182,7 +184,66 @@ static void pmaster_rounds(uint64_t seed) {
   ps_pmaster_destroy(m);
 }
 
-int main() {
+// Several threads on the same two planning contexts (a context is guarded by
+// one mutex; calls that take two contexts lock them in address order).  Each
+// thread works on jobs of its own, so every status is known.
+static void worker_thread(ps_ctx* a, ps_ctx* b, uint64_t seed, bool forward) {
+  std::mt19937_64 rng(seed);
+  const float* fake = reinterpret_cast<const float*>(uintptr_t(1) << 20);
+  for (int it = 0; it < 60; ++it) {
+    ps_ctx* src = forward ? a : b;
+    ps_ctx* dst = forward ? b : a;
+    std::vector<int64_t> layers(1 + rng() % 4);
+    for (auto& n : layers) n = 1 + (int64_t)(rng() % 9000);
+    const int32_t W = 1 + (int32_t)(rng() % 8);
+    ps_job_t job = -1, shadow = -1;
+    int32_t nb = 0, nb2 = 0;
+    CHECK(ps_register_job(src, layers.data(), (int32_t)layers.size(), W, 0.1f, 0.9f, 1e-4f, nullptr, nullptr,
+                          &job, &nb) == PS_OK);
+    CHECK(ps_register_shadow_job(dst, layers.data(), (int32_t)layers.size(), W, 0.1f, 0.9f, 1e-4f, nullptr,
+                                 &shadow, &nb2) == PS_OK);
+    CHECK(nb == nb2 && nb > 0);
+    std::vector<int32_t> ids((size_t)nb);
+    for (int32_t i = 0; i < nb; ++i) ids[(size_t)i] = i;
+    // both contexts are locked, in whatever order the two directions ask for them
+    CHECK(ps_migrate_many(src, job, ids.data(), nb, dst, shadow, nullptr) == PS_ERR_NO_DEVICE);
+    for (int32_t w = 0; w < W; ++w) CHECK(ps_push_flat(src, job, w, fake) == PS_OK);
+    int64_t need = 0;
+    CHECK(ps_pack_wave(src, &job, 1, nullptr, 0, &need) == PS_ERR_CAPACITY && need == nb);
+    std::vector<ps_block_ref> wave((size_t)need);
+    CHECK(ps_pack_wave(src, &job, 1, wave.data(), need, &need) == PS_OK);
+    ps_wave_stats st{};
+    CHECK(ps_plan_wave(src, wave.data(), need, &st) == PS_OK && st.n_blocks == nb);
+    CHECK(ps_estimate_wave(src, wave.data(), need, &st) == PS_OK && st.est_seconds > 0.0);
+    CHECK(ps_aggregate(src, wave.data(), need, nullptr) == PS_ERR_NO_DEVICE);
+    ps_block_info bi{};
+    CHECK(ps_job_block_info(src, job, nb - 1, &bi) == PS_OK && bi.W == W);
+    ps_block_stats bs{};
+    CHECK(ps_telemetry(src, job, 0, &bs) == PS_OK && bs.round == 0);
+    CHECK(ps_migrate_many(src, job, ids.data(), nb, dst, shadow, nullptr) == PS_ERR_BUSY);
+    CHECK(ps_unregister_job(dst, shadow) == PS_OK);
+    CHECK(ps_unregister_job(src, job) == PS_OK);
+  }
+}
+
+static void threaded_rounds() {
+  ps_config cfg{};
+  cfg.max_block_bytes = 4096;
+  ps_ctx *a = nullptr, *b = nullptr;
+  CHECK(ps_create(&cfg, &a) == PS_OK && ps_create(&cfg, &b) == PS_OK);
+  std::vector<std::thread> th;
+  for (int k = 0; k < 4; ++k) th.emplace_back(worker_thread, a, b, (uint64_t)(100 + k), k % 2 == 0);
+  for (auto& t : th) t.join();
+  ps_destroy(a);
+  ps_destroy(b);
+}
+
+int main(int argc, char** argv) {
+  if (argc > 1 && std::strcmp(argv[1], "threads") == 0) {
+    threaded_rounds();
+    std::printf("host thread driver: ok\n");
+    return 0;
+  }
   for (uint64_t seed = 1; seed <= 40; ++seed) service_rounds(seed);
   for (uint64_t seed = 1; seed <= 10; ++seed) scheduler_rounds(seed);
   for (uint64_t seed = 1; seed <= 10; ++seed) pmaster_rounds(seed);

@@ -1,6 +1,7 @@
 """Host code under AddressSanitizer + UBSan (CPU only): the service's planning
 paths and the scheduler through a small C++ driver, and the oracle's C++ under
-the same sanitizers through its own self-check."""
+the same sanitizers through its own self-check; the service's locking under
+ThreadSanitizer with several threads on two shared contexts."""
 import os
 import shutil
 import subprocess
@@ -29,6 +30,29 @@ def test_service_and_scheduler_host_code_is_clean_under_asan_ubsan():
         out = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=300)
         assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-4000:]
         assert "host sanitize driver: ok" in out.stdout
+
+
+@pytest.mark.skipif(shutil.which("g++") is None or not os.path.isdir("/opt/rocm/include"),
+                    reason="needs g++ and the HIP headers")
+def test_service_locking_is_clean_under_tsan():
+    """Four threads register, push, plan, estimate, inspect and unregister jobs of
+    their own on two shared contexts and ask for migrations in both directions
+    (two contexts locked per call, in address order): no data race, no lock-order
+    inversion, every status as expected."""
+    with tempfile.TemporaryDirectory() as td:
+        exe = os.path.join(td, "driver_tsan")
+        cmd = ["g++", "-std=c++17", "-fsanitize=thread", "-fno-omit-frame-pointer", "-g", "-O1",
+               "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-I", os.path.join(ROOT, "include"),
+               os.path.join(ROOT, "tests", "native", "host_sanitize_driver.cpp"),
+               os.path.join(CSRC, "ps_service.cpp"), os.path.join(CSRC, "ps_sched.cpp"),
+               os.path.join(CSRC, "ps_pmaster.cpp"),
+               "-L/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", "-lpthread", "-o", exe]
+        subprocess.check_call(cmd)
+        env = dict(os.environ, TSAN_OPTIONS="halt_on_error=1:second_deadlock_stack=1")
+        out = subprocess.run([exe, "threads"], env=env, capture_output=True, text=True, timeout=300)
+        assert out.returncode == 0, out.stdout[-2000:] + out.stderr[-4000:]
+        assert "host thread driver: ok" in out.stdout
+        assert "ThreadSanitizer" not in out.stderr
 
 
 def test_oracle_cpp_is_clean_under_asan_ubsan():
