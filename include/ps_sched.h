@@ -114,7 +114,8 @@ int32_t ps_sched_aggregators(ps_sched* s, int32_t* out_ids, int32_t cap, int32_t
 
 /* The waves of one cycle of an Aggregator, in order of start: a job that runs r
  * times per cycle appears in the waves starting at 0, 1/r, ..., (r-1)/r of the
- * cycle.  PS_ERR_CAPACITY if an output array is too small (counts still set). */
+ * cycle.  PS_ERR_CAPACITY if an output array is too small (counts still set);
+ * PS_ERR_ARG if a job would run more than 65536 times per cycle. */
 int32_t ps_sched_cycle_plan(ps_sched* s, int32_t aggregator, ps_sched_wave* out_waves,
                             int32_t cap_waves, int32_t* out_n_waves, int32_t* out_jobs,
                             int32_t cap_jobs, int32_t* out_n_jobs);

@@ -371,7 +371,9 @@ int32_t ps_sched_cycle_plan(ps_sched* s, int32_t aggregator, ps_sched_wave* out_
   };
   std::map<Key, std::vector<int32_t>> at;
   for (const auto& kv : s->aggs[aggregator].share) {
-    const int64_t r = (int64_t)std::floor(C / s->D[kv.first]);
+    const double runs = std::floor(C / s->D[kv.first]);
+    if (runs > 65536.0) return PS_ERR_ARG;  // iterations that far apart do not share a cycle plan
+    const int64_t r = (int64_t)runs;
     for (int64_t i = 0; i < r; ++i) {
       const int64_t g = std::gcd(i, r);
       at[Key{i / g, r / g}].push_back(kv.first);

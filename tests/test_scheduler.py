@@ -200,6 +200,19 @@ def test_pmaster_random_sequences_match_the_oracle(seed):
     assert sorted(o.jobs) == sorted(live)
 
 
+def test_cycle_plan_refuses_an_absurd_number_of_runs_per_cycle():
+    s = Scheduler(loss_limit=0.5)
+    fast, slow = s.add_job(1e-4), s.add_job(10.0)
+    assert s.assign(fast, 1e-6)[1] == 0 and s.assign(slow, 0.5)[1] == 0
+    with pytest.raises(PsError):
+        s.cycle_plan(0)                      # 100 000 runs of the fast job in one cycle
+    ok = Scheduler(loss_limit=0.5)
+    a, b = ok.add_job(1.0), ok.add_job(1000.0)
+    ok.assign(a, 0.01), ok.assign(b, 1.0)
+    plan = ok.cycle_plan(0)
+    assert len(plan) == 1000 and plan[0][1] == [a, b] and all(w[1] == [a] for w in plan[1:])
+
+
 def test_assignment_rate_is_job_event_scale():
     """The heuristic runs at job-event rate (Section 3.3.3: a job brings hundreds
     or thousands of model aggregations, each of which scans the Aggregators).
