@@ -64,15 +64,13 @@ void ps_pmaster_destroy(ps_pmaster* m) {
 
 int32_t ps_pmaster_add_cluster(ps_pmaster* m, double capacity, int32_t* out_cluster) try {
   if (!m || !(capacity > 0) || !std::isfinite(capacity)) return PS_ERR_ARG;
+  // room in both lists first, so that neither can be left one entry ahead of the other
+  m->controller.reserve(m->controller.size() + 1);
+  m->capacity.reserve(m->capacity.size() + 1);
   ps_sched* s = nullptr;
   const int32_t st = ps_sched_create(m->limit, &s);
   if (st != PS_OK) return st;
-  try {
-    m->controller.push_back(s);
-  } catch (...) {
-    ps_sched_destroy(s);
-    throw;
-  }
+  m->controller.push_back(s);
   m->capacity.push_back(capacity);
   if (out_cluster) *out_cluster = (int32_t)m->capacity.size() - 1;
   return PS_OK;
