@@ -391,7 +391,7 @@ def main() -> int:
         print(kernel_hash())
         return 0
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU; every block of every job lives on that GPU "
+        print("bench.py: the service runs on one GPU; every block of every job lives on that GPU "
               "and no multi-GPU path exists; run with --gpus 1.", file=sys.stderr)
         return 2
 
