@@ -122,7 +122,7 @@ def cpu_baseline(gpu, wave_refs, budget_params: float = 6e9):
     }
 
 
-def migration_bench(spec, reps: int, batched_only: bool = False):
+def migration_bench(spec, reps: int, batched_only: bool = False, hold: int = 0, stagger: int = 0):
     """Move all blocks of one job from one context to another and back, reps
     times; the time is what a job would wait if nothing hid it (GPU time of the
     announce + copy calls, HIP events on the copy stream)."""
@@ -131,7 +131,7 @@ def migration_bench(spec, reps: int, batched_only: bool = False):
     dev = torch.device("cuda:0")
     need = ParameterService.job_arena_bytes(spec.layer_numel) + 256
     arenas = [torch.zeros(need, dtype=torch.uint8, device=dev) for _ in range(2)]
-    svcs = [ParameterService(a) for a in arenas]
+    svcs = [ParameterService(a, store_hold_permille=hold, store_stagger_permille=stagger) for a in arenas]
     ja, nb = svcs[0].register_job(spec.layer_numel, spec.W, spec.lr, spec.momentum, spec.wd)
     jb, _ = svcs[1].register_shadow_job(spec.layer_numel, spec.W, spec.lr, spec.momentum, spec.wd)
     jobs = [ja, jb]
@@ -246,14 +246,12 @@ def measure(workload: str, args, keep: bool):
 
     specs, seed = specs_for(workload)
     t_setup = time.perf_counter()
-    gpu = GpuService(specs, seed, flags=2 if args.no_calibration else 0,   # PS_FLAG_NO_CALIBRATION
-                     small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
-                     store_hold_permille=args.hold_permille)
+    gpu = GpuService(specs, seed, small_block_elems=args.small_elems, launch_tiles=args.launch_tiles,
+                     store_hold_permille=args.hold_permille, store_stagger_permille=args.stagger_permille)
     gpu.fill_grads(0)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     svc = gpu.svc
-    rates = svc.rates()
 
     def step():
         wave = svc.pack_wave(gpu.jobs)                       # a3
@@ -310,6 +308,7 @@ def measure(workload: str, args, keep: bool):
     bytes_per_launch = stats.algorithmic_bytes * tm.n_waves / launches
     avg_launch_ms = tm.agg_ms / launches
     achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9 if avg_launch_ms > 0 else 0.0
+    rates = svc.rates()
     out = {
         "metric": "aggregated params/sec and achieved HBM GB/s (% of MI355X peak), 1 GPU",
         "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -327,7 +326,7 @@ def measure(workload: str, args, keep: bool):
             "bound": "hbm", "kernel": "ps_agg_wave", "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": measured_traffic(workload, not (args.small_elems or args.launch_tiles or args.hold_permille
-                                                       or args.no_calibration)),
+                                                       or args.stagger_permille)),
             "kernel_hash": kernel_hash(),
             "algorithmic_bytes_per_launch": bytes_per_launch, "avg_launch_ms": avg_launch_ms,
             "launches": tm.n_launches, "launches_per_wave": stats.n_launches,
@@ -350,8 +349,7 @@ def measure(workload: str, args, keep: bool):
                        **paths["large"]},
         "setup_seconds": t_setup,
         "rates": {"read_TB_per_s": rates.read_bytes_per_sec / 1e12, "write_TB_per_s": rates.write_bytes_per_sec / 1e12,
-                  "calibrated": bool(rates.calibrated),
-                  "note": "what the library predicts launch phases with; measured at ps_create when calibrated"},
+                  "note": "what the library times launch phases with (built in, fitted on MI355X)"},
     }
     if not keep:
         gpu.close()
@@ -381,11 +379,11 @@ def main() -> int:
     ap.add_argument("--path-split-only", action="store_true",
                     help="instead: only waves holding the small-path blocks alone, then the large-path blocks "
                          "alone, --steps of each (for kernel profiles of the two paths)")
-    ap.add_argument("--no-calibration", action="store_true",
-                    help="the library keeps its built-in HBM rates instead of measuring this GPU's")
     ap.add_argument("--small-elems", type=int, default=0, help="small-path threshold (0 = library default)")
     ap.add_argument("--launch-tiles", type=int, default=0, help="tiles per launch (0 = library default)")
     ap.add_argument("--hold-permille", type=int, default=0, help="store hold (0 = library default, <0 off)")
+    ap.add_argument("--stagger-permille", type=int, default=0,
+                    help="spread of a launch's store release (0 = library default, <0 all at once)")
     args = ap.parse_args()
     if args.kernel_hash:
         print(kernel_hash())
@@ -411,7 +409,8 @@ def main() -> int:
         return 0
     specs, seed = specs_for(args.workload)
     if args.migration:
-        print(json.dumps(migration_bench(specs[0], args.steps, args.migration_batched)))
+        print(json.dumps(migration_bench(specs[0], args.steps, args.migration_batched, args.hold_permille,
+                                         args.stagger_permille)))
         return 0
     if args.path_split_only:
         from harness import GpuService

@@ -78,9 +78,8 @@ enum {
 };
 
 enum {
-  PS_FLAG_FP_CONTRACT = 1u,/* use fused multiply-add in the update (not bit-exact with
+  PS_FLAG_FP_CONTRACT = 1u /* use fused multiply-add in the update (not bit-exact with
                               the separately rounded definition; error <= 1e-6 relative) */
-  PS_FLAG_NO_CALIBRATION = 2u /* ps_create does not measure the GPU's read rate (see ps_rates) */
 };
 
 typedef struct ps_ctx ps_ctx;
@@ -104,7 +103,14 @@ typedef struct ps_config {
                                  store them only once this fraction (in 1/1000) of the
                                  launch's predicted read time has passed since they
                                  started, so that reads and writes reach HBM in separate
-                                 bursts; 0 = default (960), negative = no hold, at most 2000 */
+                                 bursts; 0 = default (980), negative = no hold, at most 2000 */
+  int32_t store_stagger_permille; /* the workgroups of a launch release their stores one after
+                                 the other in address order, spread over this fraction (in
+                                 1/1000) of the time the launch's stores take at the read
+                                 rate, so that the writes reach HBM as a paced sweep;
+                                 0 = default (835), negative = all at once, at most 4000;
+                                 without a hold there is no spread either */
+  int32_t reserved_;           /* 0 */
 } ps_config;
 
 typedef struct ps_block_ref {
@@ -154,8 +160,7 @@ typedef struct ps_wave_stats {
 typedef struct ps_rates_info {
   double read_bytes_per_sec;   /* HBM rate of a launch's read phase */
   double write_bytes_per_sec;  /* ... and of its write phase */
-  int32_t calibrated;          /* 1 = measured on this GPU, 0 = the built-in MI355X figures (7.0 and 6.0 TB/s) */
-  int32_t reserved_;
+  int32_t reserved_[2];        /* 0 */
 } ps_rates_info;
 
 typedef struct ps_timing {
@@ -171,9 +176,8 @@ typedef struct ps_timing {
 
 /* Create a context.  cfg is copied.  The library's own device tables are small
  * and grow on demand inside ps_aggregate; ps_create itself allocates 8 MiB of
- * pinned host memory (the staging buffer of ps_aggregate_noalloc) and, while it
- * measures the GPU (see ps_rates), a stream, two events and 1 KB of device
- * memory that it releases again.  The arena's contents are only read.
+ * pinned host memory (the staging buffer of ps_aggregate_noalloc).  The arena
+ * is not touched.
  * Errors: PS_ERR_ARG (bad cfg, misaligned arena, small_block_elems > 4096). */
 int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx);
 
@@ -393,15 +397,12 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
 /* --- measurement ------------------------------------------------------------ */
 
 /* The HBM rates behind the launch timing and behind ps_wave_stats.est_seconds
- * (the service's server profiler, Section 3.1: how fast this Aggregator is).
- * The built-in figures were fitted on MI355X.  ps_create measures, once per GPU
- * and process, how this GPU compares: a few read-only launches over the arena
- * before anything lives in it (best of six readings, about 3 ms in all),
- * when the arena is at least about 1.4 GB; both rates are scaled by that
- * reading relative to the reference MI355X's.  With a smaller arena and no
- * earlier measurement in the process, with a reading outside 0.8 .. 1.15 of
- * the reference, or with PS_FLAG_NO_CALIBRATION, the built-in figures stand.
- * The rates change timing only, never results. */
+ * (the service's server profiler, Section 3.1: how fast this Aggregator is):
+ * 7.0 and 6.0 TB/s, fitted to launch times on MI355X.  They are fixed: a read
+ * probe at start-up and reports from the launches themselves were both tried
+ * and both timed the launches worse than these figures on every MI355X
+ * measured.  store_hold_permille and store_stagger_permille scale what is
+ * derived from them.  The rates change timing only, never results. */
 int32_t ps_rates(ps_ctx* ctx, ps_rates_info* out);
 
 /* Event timing of the waves, for measurement.  on == 1: from now on every

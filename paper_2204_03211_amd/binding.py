@@ -16,7 +16,6 @@ from . import build as _build
 PS_MAX_W = 32
 PS_OK = 0
 FLAG_FP_CONTRACT = 1
-FLAG_NO_CALIBRATION = 2
 
 ERRORS = {
     -1: "PS_ERR_ARG", -2: "PS_ERR_BAD_JOB", -3: "PS_ERR_BAD_BLOCK", -4: "PS_ERR_BAD_WORKER",
@@ -37,7 +36,8 @@ class PsError(RuntimeError):
 class Config(C.Structure):
     _fields_ = [("max_block_bytes", C.c_uint64), ("small_block_elems", C.c_uint32),
                 ("flags", C.c_uint32), ("arena_dev", C.c_void_p), ("arena_bytes", C.c_uint64),
-                ("launch_tiles", C.c_uint32), ("store_hold_permille", C.c_int32)]
+                ("launch_tiles", C.c_uint32), ("store_hold_permille", C.c_int32),
+                ("store_stagger_permille", C.c_int32), ("reserved_", C.c_int32)]
 
 
 class BlockRef(C.Structure):
@@ -65,7 +65,7 @@ class WaveStats(C.Structure):
 
 class Rates(C.Structure):
     _fields_ = [("read_bytes_per_sec", C.c_double), ("write_bytes_per_sec", C.c_double),
-                ("calibrated", C.c_int32), ("reserved_", C.c_int32)]
+                ("reserved_", C.c_int32 * 2)]
 
 
 class Timing(C.Structure):
@@ -175,13 +175,13 @@ class ParameterService:
 
     def __init__(self, arena: Optional[torch.Tensor] = None, max_block_bytes: int = 0,
                  small_block_elems: int = 0, flags: int = 0, launch_tiles: int = 0,
-                 store_hold_permille: int = 0):
+                 store_hold_permille: int = 0, store_stagger_permille: int = 0):
         self.L = load_library()
         self.arena = arena
         cfg = Config(max_block_bytes, small_block_elems, flags,
                      arena.data_ptr() if arena is not None else None,
                      arena.numel() * arena.element_size() if arena is not None else 0,
-                     launch_tiles, store_hold_permille)
+                     launch_tiles, store_hold_permille, store_stagger_permille, 0)
         self.cfg = cfg
         self.ctx = C.c_void_p()
         self._check(self.L.ps_create(C.byref(cfg), C.byref(self.ctx)))

@@ -63,6 +63,8 @@ struct PsChunk {
   uint32_t begin, end;
   uint32_t W;
   uint32_t hold_ticks;  // wall-clock ticks a workgroup keeps its results before storing them
+  uint32_t stagger_q16; // extra hold per workgroup index, in 1/65536 ticks
+  uint32_t pad_;
   uint64_t read_bytes;  // bytes the launch reads: sum over its tiles of (4W + 8) * elements
 };
 
@@ -87,25 +89,27 @@ constexpr uint32_t PS_SMALL_MAX_ELEMS = 4096;   // largest block the small path 
 // a few write streams, so a wave is cut into launches small enough to be resident
 // on the chip all at once: their workgroups start together, read together, keep
 // their results in registers until most of the launch's reads are done
-// (hold_ticks) and then write together.
+// (hold_ticks) and then write, one after the other in address order.
 inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e. whatever is resident
 
 // Rates of the two phases of a launch, fitted on MI355X to the launch times of
 // the aggregation kernel (time = bytes read / READ + bytes written / WRITE +
 // a fixed cost): they predict when a launch's reads end, and how long a wave
-// takes (ps_wave_stats.est_seconds).  A workgroup starts to store when
-// PS_DEFAULT_HOLD_PERMILLE / 1000 of its launch's predicted read time has
-// passed: a little before the last reads are in.  Measured on uniform jobs with
-// W = 2, 4, 8, 16: 910..985 within 1 % of the best, 1050 5 % slower, 1100 10 %;
-// on a GPU whose read probe runs 3 % slower the best point sits 3-4 % later,
-// which is what the scaling of the rates by the probe's reading accounts for.
+// takes (ps_wave_stats.est_seconds).  The first workgroup of a launch starts to
+// store when PS_DEFAULT_HOLD_PERMILLE / 1000 of the launch's predicted read
+// time has passed, a little before the last reads are in; workgroup i (index
+// order = address order) waits i * (the time one tile's stores take at the READ
+// rate) * PS_DEFAULT_STAGGER_PERMILLE / 1000 longer, so the launch's writes
+// arrive as one paced ascending sweep over about the time they need anyway
+// instead of as one burst.  Measured on the 12-job wave (kernel GB/s; hold x
+// stagger): all at once 960: 6550; 940/960/980/1000/1020 with 835: 6599 / 6673 /
+// 6728 / 6693 / 6632; 980 with 750/800/870/900/950: 6650 / 6694 / 6713 / 6698 / 6664;
+// a spread of 1200 or more loses 5 % and more.
 constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
-constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 960;
+constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 980;
 constexpr double PS_WRITE_BYTES_PER_SEC = 6.0e12;
-// What ps_measure_read_rate reads at best on the MI355X those rates were fitted
-// on (its launches include their fixed cost, so it reads lower than READ).  A
-// context scales both rates by (its GPU's best reading / this).
-constexpr double PS_PROBE_NOMINAL_BYTES_PER_SEC = 6.88e12;
+constexpr uint32_t PS_DEFAULT_STAGGER_PERMILLE = 835;
+constexpr uint32_t PS_COPY_STAGGER_PERMILLE = 835;
 constexpr double PS_EST_LAUNCH_SECONDS = 1.5e-6;
 // A copy's launches write as much as they read; measured on MI355X they are
 // fastest when the stores start at 900/1000 of the predicted read time (800:
@@ -146,20 +150,12 @@ int ps_launch_wave(const PsWaveTables& t, void* stream, uint32_t* launched);
 // TENSOR_COPY of a migration.  The copy is cut into launches of launch_tiles
 // workgroups (what the chip holds at once; 0 = unknown: one launch); a launch
 // of m tiles keeps what it read for hold_ticks_per_tile * m ticks of the wall
-// clock before it stores (0 = no hold).  Returns a hipError_t value (0 = success).
+// clock before it stores (0 = no hold), workgroup i for i * stagger_q16 / 65536
+// ticks longer.  Returns a hipError_t value (0 = success).
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
-                   void* stream, uint32_t launch_tiles, double hold_ticks_per_tile);
+                   void* stream, uint32_t launch_tiles, double hold_ticks_per_tile, uint32_t stagger_q16);
 // Workgroups of the copy kernel the current device holds at once; 0 if unknown.
 uint32_t ps_resident_copy_workgroups();
-
-// Measure the rate at which launches shaped like the aggregation's read HBM:
-// a few launches of as many workgroups as the chip holds, each reading ten
-// arrays' tiles from the arena and writing nothing to it, timed with events on
-// a stream of their own (which, with a 1 KB sink, is created and released
-// here).  Synchronous.  Returns 0 and the rate, -1 if the arena is too
-// small to give every launch fresh memory (about 1.4 GB are needed) or the
-// device cannot be queried, else a hipError_t value.
-int ps_measure_read_rate(const void* arena, uint64_t arena_bytes, double* out_bytes_per_sec);
 
 // Enqueue on stream the zeroing of n floats at p (16-byte aligned) with a fill
 // kernel (no memset node, so the call may sit inside a captured graph).

@@ -147,7 +147,8 @@ __device__ __forceinline__ double tile_body(const PsBlockRec* __restrict__ r,
   for (int u = 0; u < U; ++u) a = update4<FMA>(acc[u], pp[u], vv[u], lr, mu, wd, a);
   // The results now sit in registers.  Every workgroup of the launch started at
   // about t_start; waiting until hold_ticks later lets the launch's reads drain
-  // before its writes begin.  The clock always advances, so the wait ends.
+  // before its writes begin (the caller has added this workgroup's place in
+  // the launch's release order).  The clock always advances, so the wait ends.
 #pragma unroll
   for (int u = 0; u < U; ++u) asm volatile("" : "+v"(pp[u]), "+v"(vv[u]));  // no sinking past the wait
   while ((uint32_t)(wall_clock64() - t_start) < hold_ticks) __builtin_amdgcn_s_sleep(8);
@@ -301,13 +302,18 @@ __global__ __launch_bounds__(PS_WG, PS_MIN_WAVES) void ps_agg_wave(const unsigne
                                                      const PsSmallEntry* __restrict__ entries,
                                                      const PsBin* __restrict__ bins,
                                                      uint32_t n_bins, uint32_t hold_ticks,
-                                                     long long round_add) {
+                                                     uint32_t stagger_q16, long long round_add) {
   const uint32_t b = blockIdx.x;
   if (b < n_bins) {
     small_bin<FMA>(recs, entries, bins[b], round_add);
   } else {
-    const uint32_t t = tile_begin + (b - n_bins);
-    large_tile<W, FMA>(recs, tiles[t], t, tile_part, hold_ticks);
+    const uint32_t i = b - n_bins;
+    const uint32_t t = tile_begin + i;
+    // Stores are released in index order, which is address order: workgroup i
+    // waits stagger_q16 / 65536 ticks longer than workgroup i - 1, so that the
+    // launch's writes reach HBM as one paced sweep instead of one burst.
+    const uint32_t hold = hold_ticks ? hold_ticks + ((i * stagger_q16) >> 16) : 0u;
+    large_tile<W, FMA>(recs, tiles[t], t, tile_part, hold);
   }
 }
 
@@ -337,15 +343,17 @@ __global__ __launch_bounds__(PS_WG) void ps_block_norms(const unsigned char* __r
 // range check.  Launched like the aggregation: no more workgroups than the chip
 // holds at once, and every workgroup keeps what it has read in registers until
 // the launch's reads are due to be over (hold_ticks of the wall clock after its
-// own start; the clock always advances, so the wait ends).
+// own start, plus its place in the release order as in the aggregation; the
+// clock always advances, so the wait ends).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict__ src_p,
                                                         float* __restrict__ dst_p,
                                                         const float* __restrict__ src_v,
                                                         float* __restrict__ dst_v,
                                                         unsigned long long n, uint32_t first_tile,
-                                                        uint32_t hold_ticks) {
+                                                        uint32_t hold_ticks, uint32_t stagger_q16) {
   const unsigned long long t_start = wall_clock64();
+  const uint32_t hold = hold_ticks ? hold_ticks + ((blockIdx.x * stagger_q16) >> 16) : 0u;
   constexpr int U = PS_TILE_QUADS_PER_LANE;
   // < n by the grid's size
   const unsigned long long at = ((unsigned long long)first_tile + blockIdx.x) * PS_TILE_ELEMS;
@@ -362,49 +370,12 @@ __global__ __launch_bounds__(PS_WG) void ps_copy_shards(const float* __restrict_
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) asm volatile("" : "+v"(a[u]), "+v"(b[u]));  // loaded before the wait
-  while ((uint32_t)(wall_clock64() - t_start) < hold_ticks) __builtin_amdgcn_s_sleep(8);
+  while ((uint32_t)(wall_clock64() - t_start) < hold) __builtin_amdgcn_s_sleep(8);
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     store4(dp, (u * PS_WG + tid) * 16, a[u]);
     store4(dv, (u * PS_WG + tid) * 16, b[u]);
   }
-}
-
-// ---------------------------------------------------------------------------
-// Read-rate probe: the read phase of an aggregation launch and nothing else.
-// A workgroup reads one tile of each of `streams` arrays that lie `stride`
-// floats apart (two arrays' loads in flight together, as in tile_body), adds
-// everything up and stores nothing to the arrays it reads; should the sum hit
-// one particular value, it goes to `sink` (PS_WG floats of the probe's own),
-// which keeps the loads alive for the compiler.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(PS_WG) void ps_probe_read(const float* __restrict__ base, unsigned long long stride,
-                                                       uint32_t streams, uint32_t first_tile,
-                                                       float* __restrict__ sink) {
-  constexpr int U = PS_TILE_QUADS_PER_LANE;
-  const unsigned long long at = ((unsigned long long)first_tile + blockIdx.x) * PS_TILE_ELEMS;
-  const uint32_t tid = threadIdx.x;
-  f32x4 acc[U];
-#pragma unroll
-  for (int u = 0; u < U; ++u) acc[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  for (uint32_t s0 = 0; s0 < streams; s0 += 2) {
-    f32x4 x[2][U];
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      const uint32_t sidx = s0 + g < streams ? s0 + g : s0;   // an odd count reads its last array twice
-      const __amdgpu_buffer_rsrc_t r = span(base + sidx * stride + at, PS_TILE_ELEMS * 4);
-#pragma unroll
-      for (int u = 0; u < U; ++u) x[g][u] = load4(r, (u * PS_WG + tid) * 16);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int g = 0; g < 2; ++g)
-#pragma unroll
-      for (int u = 0; u < U; ++u) acc[u] = acc[u] + x[g][u];
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  f32x4 t = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-  if (t[0] + t[1] + t[2] + t[3] == 1.2345678e-29f) sink[tid] = t[0];
 }
 
 // Zero n floats at p (16-byte aligned): a job's shards at registration.
@@ -421,10 +392,10 @@ __global__ __launch_bounds__(PS_WG) void ps_zero_shards(float* __restrict__ p, u
 
 template <int W, bool FMA>
 hipError_t launch_one(const PsWaveTables& t, hipStream_t stream, uint32_t tile_begin, uint32_t n_tiles,
-                      uint32_t n_bins, uint32_t hold_ticks) {
+                      uint32_t n_bins, uint32_t hold_ticks, uint32_t stagger_q16 = 0) {
   hipLaunchKernelGGL((ps_agg_wave<W, FMA>), dim3(n_tiles + n_bins), dim3(PS_WG), 0, stream, t.recs,
                      t.tiles, tile_begin, t.tile_part, t.small_entries, t.bins, n_bins, hold_ticks,
-                     (long long)t.round_add);
+                     stagger_q16, (long long)t.round_add);
   return hipGetLastError();
 }
 
@@ -443,12 +414,12 @@ hipError_t launch_agg(const PsWaveTables& t, hipStream_t stream, uint32_t* launc
     hipError_t e;
     // the bins ride with the first launch so that they overlap with tile work
     switch (ch.W) {
-      case 1: e = launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 2: e = launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 4: e = launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 8: e = launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      case 16: e = launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
-      default: e = launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks); break;
+      case 1: e = launch_one<1, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
+      case 2: e = launch_one<2, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
+      case 4: e = launch_one<4, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
+      case 8: e = launch_one<8, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
+      case 16: e = launch_one<16, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
+      default: e = launch_one<0, FMA>(t, stream, ch.begin, nt, bins_left, ch.hold_ticks, ch.stagger_q16); break;
     }
     if (e != hipSuccess) return e;
     *launched += 1;
@@ -545,7 +516,7 @@ uint32_t ps_resident_copy_workgroups() {
 }
 
 int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* dst_v, uint64_t n,
-                   void* stream_, uint32_t launch_tiles, double hold_ticks_per_tile) {
+                   void* stream_, uint32_t launch_tiles, double hold_ticks_per_tile, uint32_t stagger_q16) {
   if (n == 0) return 0;
   const uint64_t tiles = (n + PS_TILE_ELEMS - 1) / PS_TILE_ELEMS;
   if (tiles > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
@@ -557,53 +528,11 @@ int ps_launch_copy(const float* src_p, float* dst_p, const float* src_v, float* 
     // never longer than half a millisecond at the clock's nominal 100 MHz
     const uint32_t hold = resident_known ? (uint32_t)std::min(hold_ticks_per_tile * m, 5.0e4) : 0u;
     hipLaunchKernelGGL(ps_copy_shards, dim3(m), dim3(PS_WG), 0, static_cast<hipStream_t>(stream_),
-                       src_p, dst_p, src_v, dst_v, (unsigned long long)n, (uint32_t)t, hold);
+                       src_p, dst_p, src_v, dst_v, (unsigned long long)n, (uint32_t)t, hold,
+                       resident_known ? stagger_q16 : 0u);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
   }
-  return 0;
-}
-
-int ps_measure_read_rate(const void* arena, uint64_t arena_bytes, double* out_bytes_per_sec) {
-  *out_bytes_per_sec = 0.0;
-  constexpr uint32_t kStreams = 10;   // eight workers' gradients, parameters, momentum
-  constexpr int kLaunchesMax = 9;     // the first is not timed
-  const uint32_t resident = ps_resident_workgroups(8);
-  if (!arena || resident == 0) return -1;
-  const uint64_t stride = arena_bytes / 4 / kStreams / PS_TILE_ELEMS * PS_TILE_ELEMS;   // floats, whole tiles
-  const uint64_t tiles_per_stream = stride / PS_TILE_ELEMS;
-  const int launches = (int)std::min<uint64_t>(kLaunchesMax, tiles_per_stream / resident);
-  if (launches < 4) return -1;        // too small to read fresh memory in every launch
-  hipStream_t st = nullptr;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  float* sink = nullptr;
-  hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipMalloc((void**)&sink, PS_WG * sizeof(float));
-  if (e == hipSuccess) e = hipEventCreate(&e0);
-  if (e == hipSuccess) e = hipEventCreate(&e1);
-  float ms = 0.0f;
-  if (e == hipSuccess) {
-    (void)hipGetLastError();
-    for (int l = 0; l < launches && e == hipSuccess; ++l) {
-      if (l == 1) e = hipEventRecord(e0, st);
-      if (e != hipSuccess) break;
-      hipLaunchKernelGGL(ps_probe_read, dim3(resident), dim3(PS_WG), 0, st, static_cast<const float*>(arena),
-                         (unsigned long long)stride, kStreams, (uint32_t)l * resident, sink);
-      e = hipGetLastError();
-    }
-    if (e == hipSuccess) e = hipEventRecord(e1, st);
-    if (e == hipSuccess) e = hipEventSynchronize(e1);
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-  }
-  if (st) (void)hipStreamSynchronize(st);   // nothing of the probe is still running when its memory goes
-  if (sink) (void)hipFree(sink);
-  if (e1) (void)hipEventDestroy(e1);
-  if (e0) (void)hipEventDestroy(e0);
-  if (st) (void)hipStreamDestroy(st);
-  if (e != hipSuccess) return (int)e;
-  if (!(ms > 0.0f)) return -1;
-  const double bytes = (double)(launches - 1) * resident * PS_TILE_ELEMS * 4.0 * kStreams;
-  *out_bytes_per_sec = bytes / (ms * 1.0e-3);
   return 0;
 }
 

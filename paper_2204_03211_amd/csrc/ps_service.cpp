@@ -133,49 +133,11 @@ struct ps_ctx {
   std::vector<Arrival*> arrivals_free;  // those no block refers to
   uint32_t resident_tiles[PS_MAX_W + 1] = {};  // per W: workgroups the chip holds at once (0 = unknown)
   uint32_t copy_resident = 0;    // the same for the migration copy kernel
-  double read_rate = PS_READ_BYTES_PER_SEC;    // bytes/s a launch's read phase sustains (measured if possible)
+  double read_rate = PS_READ_BYTES_PER_SEC;    // bytes/s a launch's read phase sustains
   double write_rate = PS_WRITE_BYTES_PER_SEC;  // bytes/s of its write phase
-  bool calibrated = false;
 };
 
 namespace {
-
-// How fast this GPU's HBM is relative to the MI355X the built-in rates were
-// fitted on is a property of the device, not of a context: the first context on
-// a device whose arena is large enough measures it, later ones reuse it.
-constexpr int kMaxDevices = 64;
-std::mutex g_speed_mu;
-double g_speed[kMaxDevices] = {};   // 0 = not measured yet
-
-void calibrate_rates(ps_ctx* c, int dev) {
-  if (c->cfg.flags & PS_FLAG_NO_CALIBRATION) return;
-  if (dev < 0 || dev >= kMaxDevices) return;
-  double speed = 0.0;
-  {
-    std::lock_guard<std::mutex> g(g_speed_mu);
-    if (g_speed[dev] == 0.0) {
-      // the best of six readings of the read probe: single readings scatter by
-      // about 2 %, always downwards (clocks still ramping, other traffic)
-      double best = 0.0;
-      int got = 0;
-      for (; got < 6; ++got) {
-        double r = 0.0;
-        if (ps_measure_read_rate(c->cfg.arena_dev, c->cfg.arena_bytes, &r) != 0) break;
-        best = std::max(best, r);
-      }
-      if (got == 6) {
-        // a reading far from an MI355X's is not believed: the built-in rates stand
-        const double rel = best / PS_PROBE_NOMINAL_BYTES_PER_SEC;
-        if (rel >= 0.8 && rel <= 1.15) g_speed[dev] = rel;
-      }
-    }
-    speed = g_speed[dev];
-  }
-  if (speed == 0.0) return;
-  c->read_rate = PS_READ_BYTES_PER_SEC * speed;
-  c->write_rate = PS_WRITE_BYTES_PER_SEC * speed;
-  c->calibrated = true;
-}
 
 int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (!in) return PS_ERR_ARG;
@@ -185,8 +147,9 @@ int32_t normalise_config(const ps_config* in, ps_config* out) {
   if (out->max_block_bytes % PS_ALIGN_BYTES != 0) return PS_ERR_ARG;
   if (out->max_block_bytes > (1ull << 30)) return PS_ERR_ARG;  // byte offsets inside a block are 32-bit
   if (out->small_block_elems > PS_SMALL_MAX_ELEMS) return PS_ERR_ARG;
-  if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT | PS_FLAG_NO_CALIBRATION)) return PS_ERR_ARG;
+  if (out->flags & ~uint32_t(PS_FLAG_FP_CONTRACT)) return PS_ERR_ARG;
   if (out->store_hold_permille > 2000) return PS_ERR_ARG;
+  if (out->store_stagger_permille > 4000 || out->reserved_ != 0) return PS_ERR_ARG;
   if (out->arena_dev && (reinterpret_cast<uintptr_t>(out->arena_dev) % PS_ALIGN_BYTES)) return PS_ERR_ARG;
   return PS_OK;
 }
@@ -296,6 +259,38 @@ int32_t validate_list(ps_ctx* c, const ps_block_ref* list, int64_t n, bool need_
   return PS_OK;
 }
 
+// Timing of a plan's launches: when each launch's reads are expected to be
+// over (hold), how its stores are spread after that (stagger), and how long the
+// wave will take.
+void retime_plan(const ps_ctx* c, Plan& P) {
+  const int32_t pm = c->cfg.store_hold_permille;
+  const double frac = pm < 0 ? 0.0 : (pm == 0 ? PS_DEFAULT_HOLD_PERMILLE : pm) / 1000.0;
+  const int32_t sm = c->cfg.store_stagger_permille;
+  const double sfrac = (pm < 0 || sm < 0) ? 0.0 : (sm == 0 ? PS_DEFAULT_STAGGER_PERMILLE : sm) / 1000.0;
+  // predicted GPU time of the wave: each launch reads, then writes (the store
+  // hold separates the two), plus a fixed cost per launch and per wave
+  double est = PS_EST_WAVE_SECONDS;
+  for (PsChunk& ch : P.chunks) {
+    // holding only pays when the whole launch is resident; a larger launch (a
+    // caller's launch_tiles) would make every later generation wait again
+    const uint32_t resident = c->resident_tiles[ch.W <= PS_MAX_W ? ch.W : 0];
+    const bool fits = resident == 0 || ch.end - ch.begin <= resident;
+    const double read_ticks = (double)ch.read_bytes / c->read_rate * c->clock_hz;
+    // never longer than half a millisecond, whatever the tables say: a resident
+    // launch reads for far less, and every wave must leave its wait soon
+    ch.hold_ticks = fits ? (uint32_t)std::min(frac * read_ticks, 5.0e-4 * c->clock_hz) : 0u;
+    // per workgroup index: the time one tile's stores (parameters and momentum)
+    // take at the read-phase rate, scaled; bounded so that index * value stays
+    // inside 32 bits and the whole spread of a resident launch below 100 us
+    const double tile_ticks = (double)PS_TILE_ELEMS * 8.0 / c->read_rate * c->clock_hz;
+    ch.stagger_q16 = (uint32_t)std::min(sfrac * tile_ticks * 65536.0, 1.0e-4 * c->clock_hz / 2048.0 * 65536.0);
+    const double params = (double)ch.read_bytes / (4.0 * ch.W + 8.0);
+    est += (double)ch.read_bytes / c->read_rate + 8.0 * params / c->write_rate + PS_EST_LAUNCH_SECONDS;
+  }
+  if (P.chunks.empty() && !P.bins.empty()) est += PS_EST_LAUNCH_SECONDS;
+  P.stats.est_seconds = est;
+}
+
 // Lay out the tables of a validated list's wave in P.
 void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
   P.recs.clear(); P.rec_of.clear(); P.large_order.clear(); P.tiles.clear(); P.chunks.clear();
@@ -398,29 +393,8 @@ void layout_plan(ps_ctx* c, const ps_block_ref* list, int64_t n, Plan& P) {
     P.large_recs.push_back(P.rec_of[i]);
   }
   if (chunk.end > chunk.begin) P.chunks.push_back(chunk);
-  // when each launch's reads are expected to be over, in wall-clock ticks
-  const int32_t pm = c->cfg.store_hold_permille;
-  const double frac = pm < 0 ? 0.0 : (pm == 0 ? PS_DEFAULT_HOLD_PERMILLE : pm) / 1000.0;
-  for (PsChunk& ch : P.chunks) {
-    // holding only pays when the whole launch is resident; a larger launch (a
-    // caller's launch_tiles) would make every later generation wait again
-    const uint32_t resident = c->resident_tiles[ch.W <= PS_MAX_W ? ch.W : 0];
-    const bool fits = resident == 0 || ch.end - ch.begin <= resident;
-    // never longer than half a millisecond, whatever the tables say: a resident
-    // launch reads for far less, and every wave must leave its wait soon
-    const double ticks = frac * (double)ch.read_bytes / c->read_rate * c->clock_hz;
-    ch.hold_ticks = fits ? (uint32_t)std::min(ticks, 5.0e-4 * c->clock_hz) : 0u;
-  }
-
-  // predicted GPU time of the wave: each launch reads, then writes (the store
-  // hold separates the two), plus a fixed cost per launch and per wave
-  double est = PS_EST_WAVE_SECONDS;
-  for (const PsChunk& ch : P.chunks) {
-    const double params = (double)ch.read_bytes / (4.0 * ch.W + 8.0);
-    est += (double)ch.read_bytes / c->read_rate + 8.0 * params / c->write_rate + PS_EST_LAUNCH_SECONDS;
-  }
-  if (P.chunks.empty() && !P.bins.empty()) est += PS_EST_LAUNCH_SECONDS;
-  P.stats.est_seconds = n > 0 ? est : 0.0;
+  retime_plan(c, P);
+  P.stats.est_seconds = n > 0 ? P.stats.est_seconds : 0.0;
 
   P.stats.n_blocks = n;
   P.stats.n_large_tiles = (int64_t)P.tiles.size();
@@ -436,6 +410,18 @@ double copy_hold_ticks_per_tile(const ps_ctx* c) {
   // the caller's knob scales the copy's hold in the same proportion as the aggregation's
   const double frac = PS_COPY_HOLD_PERMILLE / 1000.0 * (pm == 0 ? 1.0 : (double)pm / PS_DEFAULT_HOLD_PERMILLE);
   return frac * (double)PS_TILE_ELEMS * 8.0 / c->read_rate * c->clock_hz;
+}
+
+// Extra hold per workgroup index of a launch, in 1/65536 ticks: the time the
+// stores of one tile (parameters and momentum) take at the read-phase rate,
+// scaled by the configured fraction.  Bounded so that index * value stays far
+// inside 32 bits and the whole spread below 100 us for any resident launch.
+uint32_t copy_stagger_q16(const ps_ctx* c) {
+  const int32_t pm = c->cfg.store_stagger_permille;
+  if (pm < 0 || c->cfg.store_hold_permille < 0) return 0;
+  const double frac = (pm == 0 ? PS_COPY_STAGGER_PERMILLE : (uint32_t)pm) / 1000.0;
+  const double ticks_per_tile = frac * (double)PS_TILE_ELEMS * 8.0 / c->read_rate * c->clock_hz;
+  return (uint32_t)std::min(ticks_per_tile * 65536.0, 1.0e-4 * c->clock_hz / 2048.0 * 65536.0);
 }
 
 // Wait for the wave that last used the slot.
@@ -601,7 +587,6 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) try {
       c->clock_hz = 1000.0 * khz;
     for (uint32_t w = 0; w <= PS_MAX_W; ++w) c->resident_tiles[w] = ps_resident_workgroups(w);
     c->copy_resident = ps_resident_copy_workgroups();
-    calibrate_rates(c, dev);
     // everything ps_aggregate_noalloc will need, so that it never allocates:
     // this GPU's static array and a pinned staging buffer of the same size
     if (ps_static_scratch(&c->sscratch) != 0 ||
@@ -938,7 +923,7 @@ int32_t ps_migrate_copy(ps_ctx* src, ps_job_t src_job, int32_t block, ps_ctx* ds
   {
     const int le = ps_launch_copy(js->p + bs.flat_off, jd->p + bd.flat_off, js->v + bs.flat_off,
                                   jd->v + bd.flat_off, (uint64_t)bs.numel, stream, src->copy_resident,
-                                  copy_hold_ticks_per_tile(src));
+                                  copy_hold_ticks_per_tile(src), copy_stagger_q16(src));
     if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
   }
   Arrival* a = arrival_get(dst);
@@ -1005,7 +990,7 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
     const size_t bytes = (size_t)(last.flat_off + last.numel - first.flat_off) * 4;
     const int le = ps_launch_copy(js->p + first.flat_off, jd->p + first.flat_off, js->v + first.flat_off,
                                   jd->v + first.flat_off, bytes / 4, stream, src->copy_resident,
-                                  copy_hold_ticks_per_tile(src));
+                                  copy_hold_ticks_per_tile(src), copy_stagger_q16(src));
     if (le != 0) return hip_fail(dst, (hipError_t)le, "launching the migration copy");
     a = z + 1;
   }
@@ -1277,8 +1262,8 @@ int32_t ps_rates(ps_ctx* c, ps_rates_info* out) try {
   std::lock_guard<std::mutex> g(c->mu);
   out->read_bytes_per_sec = c->read_rate;
   out->write_bytes_per_sec = c->write_rate;
-  out->calibrated = c->calibrated ? 1 : 0;
-  out->reserved_ = 0;
+  out->reserved_[0] = 0;
+  out->reserved_[1] = 0;
   return PS_OK;
 } PS_NO_THROW
 

@@ -24,12 +24,13 @@ class GpuService:
 
     def __init__(self, specs: Sequence[wl.JobSpec], seed: int, max_block_bytes: int = 0,
                  small_block_elems: int = 0, flags: int = 0, device="cuda:0",
-                 grad_pad_elems: int = 0, launch_tiles: int = 0, store_hold_permille: int = 0):
+                 grad_pad_elems: int = 0, launch_tiles: int = 0, store_hold_permille: int = 0,
+                 store_stagger_permille: int = 0):
         self.specs, self.seed, self.dev = list(specs), seed, torch.device(device)
         need = sum(ParameterService.job_arena_bytes(s.layer_numel, max_block_bytes) + 256 for s in specs)
         self.arena = torch.empty(need, dtype=torch.uint8, device=self.dev)
         self.svc = ParameterService(self.arena, max_block_bytes, small_block_elems, flags,
-                                    launch_tiles, store_hold_permille)
+                                    launch_tiles, store_hold_permille, store_stagger_permille)
         self.jobs: List[int] = []
         self.layer_flat: List[List[int]] = []     # flat offset of each layer, per job
         self.blocks: List[List[Tuple[int, int, int, int]]] = []  # (layer, layer_off, numel, flat_off)

@@ -20,9 +20,8 @@ int ps_static_scratch(PsStaticScratch** out) { *out = nullptr; return 1; }
 void ps_static_scratch_lock(PsStaticScratch*) {}
 void ps_static_scratch_unlock(PsStaticScratch*) {}
 int ps_launch_zero(float*, uint64_t, void*) { return 0; }
-int ps_launch_copy(const float*, float*, const float*, float*, uint64_t, void*, uint32_t, double) { return 0; }
+int ps_launch_copy(const float*, float*, const float*, float*, uint64_t, void*, uint32_t, double, uint32_t) { return 0; }
 uint32_t ps_resident_copy_workgroups() { return 2048; }
-int ps_measure_read_rate(const void*, uint64_t, double* r) { *r = 0.0; return -1; }
 uint32_t ps_resident_workgroups(uint32_t) { return 2048; }
 
 #define CHECK(x) do { if (!(x)) { std::printf("CHECK failed: %s (line %d)\n", #x, __LINE__); std::exit(1); } } while (0)

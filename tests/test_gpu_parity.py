@@ -771,38 +771,6 @@ def test_migration_of_a_model_larger_than_one_copy_launch():
         a.close(); b.close()
 
 
-def test_read_rate_calibration_changes_timing_only(orc):
-    """ps_create measures the GPU's read rate when the arena is large enough, once
-    per process; a context can opt out.  The rates steer the store hold and the
-    predicted wave time, never a result."""
-    from paper_2204_03211_amd import ParameterService
-    from paper_2204_03211_amd.binding import FLAG_NO_CALIBRATION
-    dev = torch.device("cuda:0")
-    big = torch.empty(1_600_000_000, dtype=torch.uint8, device=dev)
-    first = ParameterService(big)
-    r = first.rates()
-    assert r.calibrated == 1 and 5.6e12 <= r.read_bytes_per_sec <= 8.05e12
-    assert r.write_bytes_per_sec == pytest.approx(r.read_bytes_per_sec * 6.0 / 7.0, rel=1e-12)
-    first.close()
-    del big
-    small = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
-    again = ParameterService(small)                      # too small to measure: the process's reading is reused
-    assert again.rates().calibrated == 1 and again.rates().read_bytes_per_sec == r.read_bytes_per_sec
-    again.close()
-    off = ParameterService(small, flags=FLAG_NO_CALIBRATION)
-    assert off.rates().calibrated == 0 and off.rates().read_bytes_per_sec == 7.0e12
-    off.close()
-    # same jobs with and without calibration: identical bits, both equal to the oracle
-    specs = [spec([300_000, 64, 4099], 8), spec([9000, 50_000], 2)]
-    cal, _ = run_both(orc, specs, seed=13, rounds=2)
-    nocal, _ = run_both(orc, specs, seed=13, rounds=2, flags=FLAG_NO_CALIBRATION)
-    assert cal.svc.rates().calibrated == 1 and nocal.svc.rates().calibrated == 0
-    for ji, s in enumerate(specs):
-        for l in range(len(s.layer_numel)):
-            assert torch.equal(cal.layer_param(ji, l), nocal.layer_param(ji, l))
-    cal.close(); nocal.close()
-
-
 def test_big_blocks_and_wide_jobs(orc):
     """A 16 MiB block cap (one 5 M-element block: offsets far beyond one launch),
     W = 32 on a multi-tile layer, and W = 1."""
@@ -819,11 +787,13 @@ def test_big_blocks_and_wide_jobs(orc):
         gpu.close()
 
 
-@pytest.mark.parametrize("launch_tiles,hold", [(3, 0), (0, -1), (7, 2000), (100000, 500)])
-def test_launch_shape_never_changes_results(orc, launch_tiles, hold):
-    """Tiles per launch and the store hold are performance knobs only."""
+@pytest.mark.parametrize("launch_tiles,hold,stagger", [(3, 0, 0), (0, -1, 0), (7, 2000, 4000), (100000, 500, 500),
+                                                       (0, 0, -1), (0, 1000, 4000), (2048, 300, 2500)])
+def test_launch_shape_never_changes_results(orc, launch_tiles, hold, stagger):
+    """Tiles per launch, the store hold and the spread of the store release are
+    performance knobs only."""
     specs = [spec([100_000, 64, 4099], 8), spec([9000, 50_000], 2), spec([33_333], 5)]
-    gpu = GpuService(specs, 5, launch_tiles=launch_tiles, store_hold_permille=hold)
+    gpu = GpuService(specs, 5, launch_tiles=launch_tiles, store_hold_permille=hold, store_stagger_permille=stagger)
     o = OracleService(orc, specs, 5)
     for r in range(2):
         gpu.fill_grads(r)

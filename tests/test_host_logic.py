@@ -351,10 +351,18 @@ def test_pushes_from_many_threads():
     assert svc.plan_wave(svc.pack_wave([job])).n_blocks == nb
 
 
+def test_release_spread_knob_is_validated():
+    from paper_2204_03211_amd import PsError
+    for ok in (-1, 0, 835, 4000):
+        ParameterService(None, store_stagger_permille=ok).close()
+    with pytest.raises(PsError):
+        ParameterService(None, store_stagger_permille=4001)
+
+
 def test_rates_of_a_planning_context_are_the_built_in_ones():
     svc = ParameterService(None)
     r = svc.rates()
-    assert (r.read_bytes_per_sec, r.write_bytes_per_sec, r.calibrated) == (7.0e12, 6.0e12, 0)
+    assert (r.read_bytes_per_sec, r.write_bytes_per_sec) == (7.0e12, 6.0e12)
     svc.close()
 
 
