@@ -35,9 +35,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # kernel sources it was measured with (kernel_hash()); with other sources the
 # figure says nothing about the loaded kernel and the line reports null.
 MEASURED_TRAFFIC = {
-    "kernel_hash": "b018151534c3baf4",
-    "per_launch": {"packed_wave": 33.9656e9 / 110, "vgg16": 6.6495e9 / 17,
-                   "resnet50": 2.0464e9 / 4, "alexnet": 2.9366e9 / 8},
+    "kernel_hash": "79f1c65da71b67a4",
+    "per_launch": {"packed_wave": 33.9588e9 / 110, "vgg16": 6.6482e9 / 17,
+                   "resnet50": 2.0463e9 / 4, "alexnet": 2.9360e9 / 8},
 }
 
 
