@@ -152,8 +152,10 @@ typedef struct ps_wave_stats {
   int64_t n_launches;      /* aggregation kernel launches the list is cut into */
   double est_seconds;      /* predicted GPU time of the wave on MI355X: per launch, bytes read
                               at the read rate, then bytes written at the write rate (ps_rates:
-                              7.0 and 6.0 TB/s unless measured), plus 1.5 us; plus 5 us a wave.  Within a few per cent of the measured time for
-                              waves of tens of megabytes and more; an execution time e_t for
+                              7.0 TB/s each), plus 1.4 us; plus 5 us a wave.  Within a few per
+                              cent of the measured time for waves of tens of megabytes and more
+                              (a planning context assumes launches of 2048 tiles, what an
+                              MI355X holds at once); an execution time e_t for
                               ps_sched_assign (the paper's profiler, Section 3.3.1) */
 } ps_wave_stats;
 
@@ -398,7 +400,7 @@ int32_t ps_migrate_many(ps_ctx* src, ps_job_t src_job, const int32_t* blocks, in
 
 /* The HBM rates behind the launch timing and behind ps_wave_stats.est_seconds
  * (the service's server profiler, Section 3.1: how fast this Aggregator is):
- * 7.0 and 6.0 TB/s, fitted to launch times on MI355X.  They are fixed: a read
+ * 7.0 TB/s each, fitted to launch times on MI355X.  They are fixed: a read
  * probe at start-up and reports from the launches themselves were both tried
  * and both timed the launches worse than these figures on every MI355X
  * measured.  store_hold_permille and store_stagger_permille scale what is

@@ -94,8 +94,9 @@ inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e
 
 // Rates of the two phases of a launch, fitted on MI355X to the launch times of
 // the aggregation kernel (time = bytes read / READ + bytes written / WRITE +
-// a fixed cost): they predict when a launch's reads end, and how long a wave
-// takes (ps_wave_stats.est_seconds).  The first workgroup of a launch starts to
+// a fixed cost; full launches of W = 2, 4, 8, 16 measure 30.3, 39.8, 59.5, 97.7
+// us, the fit gives 30.2, 39.7, 58.9, 97.3): they predict when a launch's reads
+// end, and how long a wave takes (ps_wave_stats.est_seconds).  The first workgroup of a launch starts to
 // store when PS_DEFAULT_HOLD_PERMILLE / 1000 of the launch's predicted read
 // time has passed, a little before the last reads are in; workgroup i (index
 // order = address order) waits i * (the time one tile's stores take at the READ
@@ -107,10 +108,10 @@ inline uint32_t ps_chunk_tiles(uint32_t W) { (void)W; return 1u << 20; }  // i.e
 // a spread of 1200 or more loses 5 % and more.
 constexpr double PS_READ_BYTES_PER_SEC = 7.0e12;
 constexpr uint32_t PS_DEFAULT_HOLD_PERMILLE = 980;
-constexpr double PS_WRITE_BYTES_PER_SEC = 6.0e12;
+constexpr double PS_WRITE_BYTES_PER_SEC = 7.0e12;
 constexpr uint32_t PS_DEFAULT_STAGGER_PERMILLE = 835;
 constexpr uint32_t PS_COPY_STAGGER_PERMILLE = 835;
-constexpr double PS_EST_LAUNCH_SECONDS = 1.5e-6;
+constexpr double PS_EST_LAUNCH_SECONDS = 1.4e-6;
 // A copy's launches write as much as they read; measured on MI355X they are
 // fastest when the stores start at 900/1000 of the predicted read time (800:
 // -3 %, 1000: -2 %, 1100: -6 %, no hold: -10 %).

@@ -580,6 +580,8 @@ int32_t ps_create(const ps_config* cfg, ps_ctx** out_ctx) try {
   if (!c) return PS_ERR_NOMEM;
   c->cfg = n;
   c->cap_elems = (int64_t)(n.max_block_bytes / 4);
+  // a planning context plans for the GPU the figures were fitted on: MI355X holds 2048 workgroups at once
+  for (uint32_t w = 0; w <= PS_MAX_W; ++w) c->resident_tiles[w] = 2048;
   if (n.arena_dev) {
     int dev = 0, khz = 0;
     if (hipGetDevice(&dev) == hipSuccess &&

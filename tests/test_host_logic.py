@@ -302,7 +302,7 @@ def test_pull_copy_checks_before_it_touches_the_device():
 
 
 def test_predicted_wave_time_follows_the_byte_model():
-    """est_seconds = sum over launches of read/7.0e12 + written/6.0e12 + 1.5 us, plus
+    """est_seconds = sum over launches of read/7.0e12 + written/7.0e12 + 1.4 us, plus
     5 us a wave; ps_estimate_wave reports it before any push is in."""
     svc = ParameterService(None)
     W, n = 8, 3 * (1 << 20) + 5000
@@ -313,7 +313,7 @@ def test_predicted_wave_time_follows_the_byte_model():
     assert ei.value.name == "PS_ERR_NOT_READY"
     st = svc.estimate_wave(wave)
     large = n                                                 # the 100-element layer rides in a bin
-    want = 5e-6 + st.n_launches * 1.5e-6 + (4 * W + 8) * large * 4 / 4 / 7.0e12 + 8 * large / 6.0e12
+    want = 5e-6 + st.n_launches * 1.4e-6 + (4 * W + 8) * large * 4 / 4 / 7.0e12 + 8 * large / 7.0e12
     assert st.n_launches == 1 and st.n_small_blocks == 1
     assert st.est_seconds == pytest.approx(want, rel=1e-9)
     assert svc.estimate_wave(WaveList([])).est_seconds == 0.0
@@ -362,7 +362,7 @@ def test_release_spread_knob_is_validated():
 def test_rates_of_a_planning_context_are_the_built_in_ones():
     svc = ParameterService(None)
     r = svc.rates()
-    assert (r.read_bytes_per_sec, r.write_bytes_per_sec) == (7.0e12, 6.0e12)
+    assert (r.read_bytes_per_sec, r.write_bytes_per_sec) == (7.0e12, 7.0e12)
     svc.close()
 
 
