@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # kernel sources it was measured with (kernel_hash()); with other sources the
 # figure says nothing about the loaded kernel and the line reports null.
 MEASURED_TRAFFIC = {
-    "kernel_hash": "79f1c65da71b67a4",
-    "per_launch": {"packed_wave": 33.9588e9 / 110, "vgg16": 6.6482e9 / 17,
+    "kernel_hash": "455f0af7709df7ad",
+    "per_launch": {"packed_wave": 33.9590e9 / 110, "vgg16": 6.6483e9 / 17,
                    "resnet50": 2.0463e9 / 4, "alexnet": 2.9360e9 / 8},
 }
 
